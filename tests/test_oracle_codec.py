@@ -1,0 +1,341 @@
+"""Pins of the CPU oracle's block codec (Sec. 3.1 of the paper: symmetric
+quantization of each block with its own scale) against things other than
+itself: closed forms, IEEE-754 evaluated by a different route (tests/ref64.py),
+numpy/torch conversions, invariants, brute force over every fp16 value."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import F16, BF16, F32
+import ref64
+
+
+def f16_bits(vals):
+    return np.asarray(vals, dtype=np.float16).view(np.uint16)
+
+
+def bf16_bits(vals):
+    t = torch.tensor(np.asarray(vals, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+def to_bits(vals, dtype):
+    if dtype == F16:
+        return f16_bits(vals)
+    if dtype == BF16:
+        return bf16_bits(vals)
+    return np.asarray(vals, dtype=np.float32)
+
+
+# ----------------------------------------------------------------------------
+# storage-format conversions against numpy / torch
+# ----------------------------------------------------------------------------
+
+def test_widen_f16_every_pattern_matches_numpy():
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.widen(bits, F16)
+    want = bits.view(np.float16).astype(np.float32)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+
+
+def test_widen_bf16_every_pattern_matches_torch():
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.widen(bits, BF16)
+    want = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).to(torch.float32).numpy()
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+
+
+def _narrow_probe_values():
+    rng = np.random.default_rng(7)
+    v = [rng.standard_normal(20000).astype(np.float32) * s for s in (1e-8, 1e-5, 1e-3, 1.0, 300.0, 7e4)]
+    # every fp16 value, its neighbours in fp32, and the exact midpoints between fp16 neighbours
+    h = np.arange(0x7C00, dtype=np.uint16).view(np.float16).astype(np.float32)
+    mid = ((h[:-1].astype(np.float64) + h[1:].astype(np.float64)) / 2).astype(np.float32)
+    v += [h, np.nextafter(h, np.float32(np.inf)), np.nextafter(h, np.float32(-np.inf)), mid,
+          np.nextafter(mid, np.float32(np.inf)), np.nextafter(mid, np.float32(0))]
+    v += [np.array([65504.0, 65519.0, 65519.99, 65520.0, 65536.0, 1e30, 0.0, -0.0,
+                    2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * 1.0000001, 2.0 ** -26, 1e-45], dtype=np.float32)]
+    v = np.concatenate(v)
+    return np.concatenate([v, -v])
+
+
+def test_narrow_f16_matches_numpy_rounding():
+    v = _narrow_probe_values()
+    with np.errstate(over="ignore"):
+        want = v.astype(np.float16).view(np.uint16)
+    assert np.array_equal(oracle.narrow(v, F16), want)
+
+
+def test_narrow_bf16_matches_torch_rounding():
+    v = _narrow_probe_values()
+    b = np.arange(0, 0x7F80, 37, dtype=np.uint16)
+    bf = torch.from_numpy(b.view(np.int16).copy()).view(torch.bfloat16).to(torch.float32).numpy()
+    mids = ((bf[:-1].astype(np.float64) + bf[1:].astype(np.float64)) / 2).astype(np.float32)
+    v = np.concatenate([v, bf, mids, -mids])
+    want = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.narrow(v, BF16), want)
+
+
+# ----------------------------------------------------------------------------
+# closed forms
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dtype", [F16, BF16, F32])
+@pytest.mark.parametrize("e", [-10, 0, 3])
+def test_power_of_two_grid_is_coded_exactly(bits, dtype, e):
+    """Values k*2^e with max|k| = qmax: scale = 2^e, codes = k, decode = input."""
+    qmax = ref64.qmax_of(bits)
+    block = 2 * qmax + 2 if bits == 8 else 32
+    ks = np.arange(-qmax, qmax + 1)
+    ks = np.resize(ks, block)                       # every code value appears
+    rng = np.random.default_rng(bits + e + 100)
+    blocks = [rng.permutation(ks) for _ in range(5)]
+    k = np.concatenate(blocks)
+    x = to_bits(k * 2.0 ** e, dtype)
+    codes, scales = oracle.qwz_quantize(x, dtype, block, bits)
+    assert np.array_equal(scales, np.full(5, 2.0 ** e, dtype=np.float32))
+    assert np.array_equal(oracle.unpack_codes(codes, k.size, bits), k)
+    y = oracle.qwz_dequantize(codes, scales, k.size, block, bits, dtype)
+    assert np.array_equal(y, x)
+
+
+def test_int4_byte_layout_low_nibble_first():
+    """Raw bytes of a hand-made block: element 2i in bits 0-3, 2i+1 in bits 4-7."""
+    k = np.zeros(32, dtype=np.int64)
+    k[:8] = [7, -7, 1, -1, 0, 3, -4, 2]
+    codes, scales = oracle.qwz_quantize(f16_bits(k * 0.5), F16, 32, 4)
+    assert scales[0] == np.float32(0.5)
+    assert list(codes[:4]) == [0x97, 0xF1, 0x30, 0x2C]
+    assert np.array_equal(ref64.unpack_nibbles(codes, 32), k)
+
+
+def test_int8_byte_layout_twos_complement():
+    k = np.zeros(32, dtype=np.int64)
+    k[:4] = [127, -127, -1, 5]
+    codes, _ = oracle.qwz_quantize(f16_bits(k * 2.0), F16, 32, 8)
+    assert list(codes[:4]) == [0x7F, 0x81, 0xFF, 0x05]
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_ties_round_to_even(bits):
+    """absmax = qmax*2^e makes inv = 2^-e exactly, so (k+1/2)*2^e lands exactly
+    on a tie; the code must be the even neighbour (not away-from-zero, not
+    truncation)."""
+    qmax = ref64.qmax_of(bits)
+    ks = np.arange(-qmax, qmax)               # k + 0.5 in (-qmax, qmax)
+    halves = ks + 0.5
+    vals = np.concatenate([[float(qmax)], halves])
+    block = 32 * ((vals.size + 31) // 32)
+    v = np.zeros(block)
+    v[:vals.size] = vals
+    codes, scales = oracle.qwz_quantize(to_bits(v * 4.0, F32), F32, block, bits)
+    assert scales[0] == np.float32(4.0)
+    got = oracle.unpack_codes(codes, block, bits)[1:1 + halves.size]
+    want = np.where(ks % 2 == 0, ks, ks + 1)  # the even one of k, k+1
+    assert np.array_equal(got, want)
+    assert not np.array_equal(want, np.trunc(halves))
+    assert not np.array_equal(want, np.sign(halves) * np.floor(np.abs(halves) + 0.5))
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_scale_is_correctly_rounded_quotient_exact_rational(bits):
+    """scale = RN(absmax / qmax), checked with exact rational arithmetic."""
+    qmax = ref64.qmax_of(bits)
+    rng = np.random.default_rng(11)
+    a = np.abs(rng.standard_normal(300).astype(np.float32)) * np.float32(0.02) + np.float32(1e-6)
+    x = np.zeros((300, 32), dtype=np.float32)
+    x[:, 5] = a
+    x[:, 6] = -a / 3
+    _, scales = oracle.qwz_quantize(x, F32, 32, bits)
+    for ai, si in zip(a, scales):
+        assert float(si) == ref64.round_fraction_to_f32(Fraction(float(ai)) / qmax)
+
+
+# ----------------------------------------------------------------------------
+# brute force: every finite fp16 value, against the float64-route evaluator
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_every_finite_fp16_value_matches_second_evaluator(bits):
+    pats = np.arange(65536, dtype=np.uint16)
+    finite = (pats & 0x7C00) != 0x7C00
+    pats = pats[finite]                                   # 63488 values = 1984 blocks of 32
+    rng = np.random.default_rng(3)
+    for order in (pats, rng.permutation(pats), rng.permutation(pats)):
+        codes, scales = oracle.qwz_quantize(order, F16, 32, bits)
+        q_ref, s_ref = ref64.quant_blocks(ref64.f16_bits_to_f64(order), 32, bits)
+        assert np.array_equal(scales.view(np.uint32), s_ref.view(np.uint32))
+        assert np.array_equal(oracle.unpack_codes(codes, order.size, bits), q_ref)
+        # decode, fp32 and fp16 outputs
+        d_ref = ref64.dequant(q_ref, s_ref, 32)
+        d32 = oracle.qwz_dequantize(codes, scales, order.size, 32, bits, F32)
+        assert np.array_equal(d32.astype(np.float64), d_ref)
+        d16 = oracle.qwz_dequantize(codes, scales, order.size, 32, bits, F16)
+        assert np.array_equal(d16, d_ref.astype(np.float32).astype(np.float16).view(np.uint16))
+
+
+@pytest.mark.parametrize("bits,block", [(8, 256), (8, 2048), (4, 512), (4, 32), (8, 96)])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_random_tensors_match_second_evaluator(bits, block, dtype):
+    rng = np.random.default_rng(block + bits)
+    n = block * 37
+    v = rng.standard_normal(n) * 0.02
+    v[rng.random(n) < 1e-2] *= 20
+    x = to_bits(v, dtype)
+    codes, scales = oracle.qwz_quantize(x, dtype, block, bits)
+    q_ref, s_ref = ref64.quant_blocks(ref64.widen64(x, dtype), block, bits)
+    assert np.array_equal(scales.view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(oracle.unpack_codes(codes, n, bits), q_ref)
+    y = oracle.qwz_dequantize(codes, scales, n, block, bits, dtype)
+    d = ref64.dequant(q_ref, s_ref, block).astype(np.float32)
+    want = d.astype(np.float16).view(np.uint16) if dtype == F16 else bf16_bits(d)
+    assert np.array_equal(y, want)
+
+
+# ----------------------------------------------------------------------------
+# invariants
+# ----------------------------------------------------------------------------
+
+def _weights_like(n, seed, dtype):
+    from paper_2306_10209_amd import workloads
+    tdt = torch.float16 if dtype == F16 else torch.bfloat16
+    return workloads.as_bits(workloads.weights(n, seed=seed, dtype=tdt))
+
+
+def _grads_like(n, seed):
+    from paper_2306_10209_amd import workloads
+    return workloads.as_bits(workloads.gradients(n, seed=seed))
+
+
+@pytest.mark.parametrize("bits,block,dtype", [(8, 256, F16), (8, 2048, BF16), (4, 512, F16)])
+def test_absmax_element_gets_extreme_code(bits, block, dtype):
+    qmax = ref64.qmax_of(bits)
+    n = block * 512
+    x = _grads_like(n, 5) if bits == 4 else _weights_like(n, 5, dtype)
+    codes, _ = oracle.qwz_quantize(x, dtype, block, bits)
+    q = oracle.unpack_codes(codes, n, bits).reshape(-1, block)
+    v = ref64.widen64(x, dtype).reshape(-1, block)
+    a = np.max(np.abs(v), axis=1, keepdims=True)
+    at_max = np.abs(v) == a
+    assert np.array_equal(q[at_max], (np.sign(v) * qmax)[at_max].astype(np.int32))
+    assert np.max(np.abs(q)) == qmax and np.all(np.max(np.abs(q), axis=1) == qmax)
+
+
+@pytest.mark.parametrize("bits,block,dtype,eps", [(8, 256, F16, 2.0 ** -14), (8, 2048, BF16, 2.0 ** -14),
+                                                  (4, 512, F16, 2.0 ** -18)])
+def test_reconstruction_error_within_half_a_step(bits, block, dtype, eps):
+    """|x - q*scale| <= scale/2 (Sec. 3.1's point: the step is set by the block's
+    own range).  The two fp32 roundings on the encode side allow a slop eps."""
+    n = block * 512
+    x = _grads_like(n, 6) if bits == 4 else _weights_like(n, 6, dtype)
+    codes, scales = oracle.qwz_quantize(x, dtype, block, bits)
+    q = oracle.unpack_codes(codes, n, bits).astype(np.float64).reshape(-1, block)
+    v = ref64.widen64(x, dtype).reshape(-1, block)
+    s = scales.astype(np.float64)[:, None]
+    err = np.abs(v - q * s)
+    assert np.all(err <= s * (0.5 + eps))
+    assert np.mean(err > s * 0.5) < 1e-3
+
+
+@pytest.mark.parametrize("bits,block,dtype", [(8, 256, F16), (4, 512, F16), (8, 2048, F32)])
+def test_requantizing_decoded_values_returns_the_codes(bits, block, dtype):
+    n = block * 256
+    x = _grads_like(n, 8) if bits == 4 else _weights_like(n, 8, F16)
+    codes, scales = oracle.qwz_quantize(x, F16, block, bits)
+    y = oracle.qwz_dequantize(codes, scales, n, block, bits, dtype)
+    codes2, _ = oracle.qwz_quantize(y, dtype, block, bits)
+    assert np.array_equal(codes, codes2)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_zero_and_tiny_blocks(bits):
+    block = 64
+    x = np.zeros(4 * block, dtype=np.float32)
+    x[block:2 * block] = 2.0 ** -101            # below the threshold: treated as zero
+    x[2 * block] = 2.0 ** -100                  # at the threshold: quantized normally
+    x[3 * block:] = -0.0
+    codes, scales = oracle.qwz_quantize(x, F32, block, bits)
+    qmax = ref64.qmax_of(bits)
+    assert scales[0] == 0 and scales[1] == 0 and scales[3] == 0
+    assert scales[2] == np.float32(2.0 ** -100 / qmax)
+    q = oracle.unpack_codes(codes, x.size, bits).reshape(4, block)
+    assert not q[0].any() and not q[1].any() and not q[3].any()
+    assert q[2, 0] == qmax and not q[2, 1:].any()
+    y = oracle.qwz_dequantize(codes, scales, x.size, block, bits, F32)
+    assert np.array_equal(y[:2 * block].view(np.uint32), np.zeros(2 * block, dtype=np.uint32))  # +0 exactly
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_blocks_are_independent_and_shards_concatenate(bits):
+    block, nb = 128, 64
+    x = _weights_like(block * nb, 9, BF16)
+    codes, scales = oracle.qwz_quantize(x, BF16, block, bits)
+    # perturb one block: nothing else moves
+    x2 = x.copy()
+    x2[5 * block + 3] = bf16_bits([3.0])[0]
+    codes2, scales2 = oracle.qwz_quantize(x2, BF16, block, bits)
+    cb = block * bits // 8
+    same = np.ones(nb, dtype=bool)
+    same[5] = False
+    assert np.array_equal(codes.reshape(nb, cb)[same], codes2.reshape(nb, cb)[same])
+    assert np.array_equal(scales[same], scales2[same]) and scales[5] != scales2[5]
+    # quantizing P shards separately and concatenating == quantizing the whole tensor
+    parts = [oracle.qwz_quantize(s, BF16, block, bits) for s in np.split(x, 8)]
+    assert np.array_equal(np.concatenate([p[0] for p in parts]), codes)
+    assert np.array_equal(np.concatenate([p[1] for p in parts]), scales)
+
+
+def test_decode_of_largest_fp16_does_not_overflow():
+    x = np.zeros(256, dtype=np.float16)
+    x[0], x[1], x[2] = 65504.0, -65504.0, 30000.0
+    for bits in (8, 4):
+        codes, scales = oracle.qwz_quantize(x.view(np.uint16), F16, 256, bits)
+        y = oracle.qwz_dequantize(codes, scales, 256, 256, bits, F16).view(np.float16)
+        assert y[0] == np.float16(65504.0) and y[1] == np.float16(-65504.0)
+        assert np.all(np.isfinite(y))
+
+
+def test_code_sizes_reproduce_the_papers_volume_ratios(golden_dir):
+    """Sec. 3.4 / Table 1: int8 halves and int4 quarters the fp16 volume."""
+    import os
+    rows = [l.split() for l in open(os.path.join(golden_dir, "comm_volume.txt")) if l[0] != "#"]
+    n = 1 << 20
+    for _name, bits, ratio in rows:
+        assert oracle.codes_nbytes(n, int(bits)) == float(ratio) * 2 * n
+    # 3M -> 0.5M + 0 + 0.25M = 0.75M: the 4x headline
+    assert (oracle.codes_nbytes(n, 8) + oracle.codes_nbytes(n, 4)) / (3 * 2 * n) == 0.25
+
+
+def test_invalid_arguments_are_rejected():
+    x = np.zeros(100, dtype=np.uint16)
+    with pytest.raises(oracle.OracleError):
+        oracle.qwz_quantize(x, F16, 32, 8)          # n % block != 0
+    with pytest.raises(oracle.OracleError):
+        oracle.qwz_quantize(x[:96], F16, 32, 5)     # bits
+    with pytest.raises(oracle.OracleError):
+        oracle.qwz_quantize(x[:96], 7, 32, 8)       # dtype
+
+
+def test_thread_count_does_not_change_results():
+    n, block = 512 * 200, 512
+    x = _grads_like(n, 12)
+    before = oracle.set_threads(0)
+    try:
+        oracle.set_threads(1)
+        a = oracle.qwz_quantize(x, F16, block, 4)
+        ra = oracle.qgz_intra_reduce([a[0]] * 3, [a[1]] * 3, n, block, 4)
+        oracle.set_threads(4)
+        b = oracle.qwz_quantize(x, F16, block, 4)
+        rb = oracle.qgz_intra_reduce([b[0]] * 3, [b[1]] * 3, n, block, 4)
+    finally:
+        oracle.set_threads(before)
+    for u, v in zip(a + ra, b + rb):
+        assert np.array_equal(u.view(np.uint8), v.view(np.uint8))
