@@ -1,0 +1,167 @@
+"""Thin ctypes binding of libzpp_gfx950.so (include/zpp.h).
+
+Argument marshalling only: torch supplies device memory and the stream, every
+step of the computation runs in the library's kernels.  There is no fallback: if
+the shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+F16, BF16, F32 = 0, 1, 2
+MAX_PEERS = 64
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "lib", "libzpp_gfx950.so")
+
+EXPORTS = ("zpp_codes_bytes", "zpp_scales_count", "zpp_strerror", "zpp_reorder_source_slice",
+           "zpp_reorder_mapped_slice", "qwz_quantize", "qwz_dequantize", "qgz_reorder",
+           "qgz_intra_reduce", "qgz_inter_reduce", "zpp_stream_copy")
+
+_lib = None
+
+
+class ZppError(RuntimeError):
+    pass
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built (run
+    `python -m paper_2306_10209_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ZppError(f"{LIB_PATH} is missing: build it with `python -m paper_2306_10209_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.zpp_codes_bytes.argtypes, L.zpp_codes_bytes.restype = [sz, ci], sz
+        L.zpp_scales_count.argtypes, L.zpp_scales_count.restype = [sz, ci], sz
+        L.zpp_strerror.argtypes, L.zpp_strerror.restype = [ci], ctypes.c_char_p
+        for f in (L.zpp_reorder_source_slice, L.zpp_reorder_mapped_slice):
+            f.argtypes, f.restype = [ctypes.c_longlong, ci, ci, ci], ctypes.c_longlong
+        L.qwz_quantize.argtypes = [vp, ci, sz, ci, ci, vp, vp, vp]
+        L.qwz_dequantize.argtypes = [vp, vp, sz, ci, ci, ci, vp, vp]
+        L.qgz_reorder.argtypes = [vp, ci, sz, ci, ci, ci, ci, ci, vp, vp, vp]
+        L.qgz_intra_reduce.argtypes = [vp, vp, ci, sz, ci, ci, vp, vp, vp]
+        L.qgz_inter_reduce.argtypes = [vp, vp, ci, sz, ci, ci, ctypes.c_float, vp, vp]
+        L.zpp_stream_copy.argtypes = [vp, vp, sz, vp]
+        for name in ("qwz_quantize", "qwz_dequantize", "qgz_reorder", "qgz_intra_reduce",
+                     "qgz_inter_reduce", "zpp_stream_copy"):
+            getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def _check(rc, name):
+    if rc != 0:
+        raise ZppError(f"{name}: {lib().zpp_strerror(rc).decode()} (rc={rc})")
+
+
+def dtype_code(t):
+    try:
+        return {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[t]
+    except KeyError:
+        raise ZppError(f"unsupported dtype {t}") from None
+
+
+def torch_dtype(code):
+    return {F16: torch.float16, BF16: torch.bfloat16, F32: torch.float32}[code]
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ZppError(f"{name}: needs a contiguous device tensor")
+    return t.data_ptr()
+
+
+def codes_bytes(n, bits):
+    return int(lib().zpp_codes_bytes(n, bits))
+
+
+def scales_count(n, block):
+    return int(lib().zpp_scales_count(n, block))
+
+
+def reorder_source_slice(p, X, Y, S=1):
+    return int(lib().zpp_reorder_source_slice(p, X, Y, S))
+
+
+def reorder_mapped_slice(pid, X, Y, S=1):
+    return int(lib().zpp_reorder_mapped_slice(pid, X, Y, S))
+
+
+def qwz_quantize(x, block, bits=8, codes=None, scales=None, stream=None):
+    """Block-quantize the flat tensor x.  `codes` (uint8) / `scales` (float32) may be
+    views into a larger buffer (a shard's slot of the gather buffer)."""
+    n = x.numel()
+    if codes is None:
+        codes = torch.empty(n * bits // 8, dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(n // block if block > 0 else 0, dtype=torch.float32, device=x.device)
+    _check(lib().qwz_quantize(_dev(x, "x"), dtype_code(x.dtype), n, block, bits, _dev(codes, "codes"),
+                              _dev(scales, "scales"), _stream(stream)), "qwz_quantize")
+    return codes, scales
+
+
+def qwz_dequantize(codes, scales, n, block, bits=8, out_dtype=torch.float16, out=None, stream=None):
+    if out is None:
+        out = torch.empty(n, dtype=out_dtype, device=codes.device)
+    _check(lib().qwz_dequantize(_dev(codes, "codes"), _dev(scales, "scales"), n, block, bits,
+                                dtype_code(out.dtype), _dev(out, "out"), _stream(stream)), "qwz_dequantize")
+    return out
+
+
+def qgz_reorder(grad, X, Y, S, block, bits=4, codes=None, scales=None, stream=None):
+    n = grad.numel()
+    if codes is None:
+        codes = torch.empty(n * bits // 8, dtype=torch.uint8, device=grad.device)
+    if scales is None:
+        scales = torch.empty(n // block if block > 0 else 0, dtype=torch.float32, device=grad.device)
+    _check(lib().qgz_reorder(_dev(grad, "grad"), dtype_code(grad.dtype), n, X, Y, S, block, bits,
+                             _dev(codes, "codes"), _dev(scales, "scales"), _stream(stream)), "qgz_reorder")
+    return codes, scales
+
+
+def _table(tensors, name):
+    if len(tensors) == 0:
+        raise ZppError(f"{name}: empty pointer table")
+    arr = (ctypes.c_void_p * len(tensors))(*[_dev(t, name) for t in tensors])
+    return arr
+
+
+def qgz_intra_reduce(codes_in, scales_in, m, block, bits=4, codes_out=None, scales_out=None, stream=None):
+    _table(codes_in, "codes_in")
+    dev = codes_in[0].device
+    if codes_out is None:
+        codes_out = torch.empty(m * bits // 8, dtype=torch.uint8, device=dev)
+    if scales_out is None:
+        scales_out = torch.empty(m // block if block > 0 else 0, dtype=torch.float32, device=dev)
+    _check(lib().qgz_intra_reduce(_table(codes_in, "codes_in"), _table(scales_in, "scales_in"), len(codes_in),
+                                  m, block, bits, _dev(codes_out, "codes_out"), _dev(scales_out, "scales_out"),
+                                  _stream(stream)), "qgz_intra_reduce")
+    return codes_out, scales_out
+
+
+def qgz_inter_reduce(codes_in, scales_in, m, block, bits=4, divisor=1.0, out=None, stream=None):
+    _table(codes_in, "codes_in")
+    dev = codes_in[0].device
+    if out is None:
+        out = torch.empty(m, dtype=torch.float32, device=dev)
+    _check(lib().qgz_inter_reduce(_table(codes_in, "codes_in"), _table(scales_in, "scales_in"), len(codes_in),
+                                  m, block, bits, float(divisor), _dev(out, "out"), _stream(stream)),
+           "qgz_inter_reduce")
+    return out
+
+
+def stream_copy(dst, src, stream=None):
+    """Measurement helper: plain 16-byte-per-lane device copy."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().zpp_stream_copy(_dev(dst, "dst"), _dev(src, "src"), nbytes, _stream(stream)), "zpp_stream_copy")
+    return dst

@@ -1,0 +1,821 @@
+// libzpp_gfx950: HIP kernels for AMD MI355X (gfx950, wave64) of the compute that
+// ZeRO++ (arxiv 2306.10209) wraps around its collectives, and their C ABI
+// (include/zpp.h).  Everything here is streaming work bound by HBM bandwidth or
+// by plain vector ALU issue, so there is no matrix-core code: lanes move 16-byte
+// vectors, block maxima are folded with DPP / swizzle lane exchanges, and codes
+// are packed in registers before a single coalesced store.
+//
+// Arithmetic contract (see zpp.h): fp32, one rounding per operation, built with
+// -ffp-contract=off.  Where a fused multiply-add appears below it is written
+// explicitly and computes a single correctly rounded product (the addend only
+// removes a bias exactly), so results stay bit-identical to the plain formulas.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "zpp.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kWavesPerWG = 4;
+constexpr int kThreads = kWave * kWavesPerWG;
+constexpr float kTiny = 0x1p-100f;  // blocks with a smaller maximum are coded as all zero
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// ---------------------------------------------------------------------------
+// lane exchanges for the per-block maximum
+// ---------------------------------------------------------------------------
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    int i = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false));
+}
+
+// Maximum over aligned groups of G consecutive lanes (G a power of two), left in
+// every lane of the group.  Values are non-negative finite floats.
+template <int G>
+__device__ __forceinline__ float group_max(float v)
+{
+    if (G >= 2) v = fmaxf(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
+    if (G >= 4) v = fmaxf(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
+    if (G >= 8) v = fmaxf(v, dpp_mov<0x141>(v));   // row_half_mirror
+    if (G >= 16) v = fmaxf(v, dpp_mov<0x140>(v));  // row_mirror
+    if (G >= 32) {                                 // ds_swizzle: lane ^ 16 inside each half wave
+        int i = __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F);
+        v = fmaxf(v, __builtin_bit_cast(float, i));
+    }
+    if (G >= 64) v = fmaxf(v, __shfl_xor(v, 32, 64));
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// storage types
+// ---------------------------------------------------------------------------
+
+// Two packed 16-bit values of a dword -> fp32 (exact).
+template <int DT>
+__device__ __forceinline__ void widen2(uint32_t w, float& lo, float& hi)
+{
+    if (DT == ZPP_F16) {
+        lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
+        hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+    } else {
+        lo = as_f32(w << 16);
+        hi = as_f32(w & 0xffff0000u);
+    }
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t bf16_rne(float f)
+{
+    uint32_t u = as_u32(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t narrow2(float lo, float hi)
+{
+    if (DT == ZPP_F16) {
+        uint32_t a = __builtin_bit_cast(uint16_t, (_Float16)lo);
+        uint32_t b = __builtin_bit_cast(uint16_t, (_Float16)hi);
+        return a | (b << 16);
+    } else {
+        return bf16_rne(lo) | (bf16_rne(hi) << 16);
+    }
+}
+
+// Eight consecutive elements of a DT tensor starting at element index `e` (a
+// multiple of 8), widened to fp32.
+template <int DT>
+__device__ __forceinline__ void load8(const void* __restrict__ base, uint64_t e, float (&f)[8])
+{
+    if (DT == ZPP_F32) {
+        const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + e);
+        f32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+        f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    } else {
+        const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + e);
+        u32x4 w = __builtin_nontemporal_load(p);
+        widen2<DT>(w.x, f[0], f[1]);
+        widen2<DT>(w.y, f[2], f[3]);
+        widen2<DT>(w.z, f[4], f[5]);
+        widen2<DT>(w.w, f[6], f[7]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// block codec pieces
+// ---------------------------------------------------------------------------
+
+template <int BITS>
+struct Q {
+    static constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
+};
+
+// scale and encode multiplier of a block whose maximum magnitude is `a`
+template <int BITS>
+__device__ __forceinline__ void block_scale(float a, float& scale, float& inv)
+{
+    if (a < kTiny) {
+        scale = 0.0f;
+        inv = 0.0f;  // every product is +-0 -> code 0
+    } else {
+        scale = a / Q<BITS>::qmax;
+        inv = Q<BITS>::qmax / a;
+    }
+}
+
+// Code of one value: roundeven(v * inv).  Adding 1.5*2^23 rounds the product to
+// an integer with the adder's own round-to-nearest-even and leaves it, in two's
+// complement, in the low mantissa bits.  |v*inv| <= qmax + 2^-17 for finite
+// input, so no clamp is needed.
+__device__ __forceinline__ uint32_t code_bits(float v, float inv)
+{
+    float t = v * inv;
+    return as_u32(t + 12582912.0f);
+}
+
+// eight codes -> packed storage
+template <int BITS>
+__device__ __forceinline__ void store_codes8(uint8_t* __restrict__ codes, uint64_t e, const float (&f)[8], float inv)
+{
+    uint32_t c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = code_bits(f[i], inv);
+    if (BITS == 8) {
+        u32x2 o;
+        o.x = (c[0] & 0xffu) | ((c[1] & 0xffu) << 8) | ((c[2] & 0xffu) << 16) | (c[3] << 24);
+        o.y = (c[4] & 0xffu) | ((c[5] & 0xffu) << 8) | ((c[6] & 0xffu) << 16) | (c[7] << 24);
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(codes + e));
+    } else {
+        uint32_t o = (c[0] & 0xfu) | ((c[1] & 0xfu) << 4) | ((c[2] & 0xfu) << 8) | ((c[3] & 0xfu) << 12) |
+                     ((c[4] & 0xfu) << 16) | ((c[5] & 0xfu) << 20) | ((c[6] & 0xfu) << 24) | (c[7] << 28);
+        __builtin_nontemporal_store(o, reinterpret_cast<uint32_t*>(codes + (e >> 1)));
+    }
+}
+
+__device__ __forceinline__ float absmax8(const float (&f)[8])
+{
+    float m = fabsf(f[0]);
+#pragma unroll
+    for (int i = 1; i < 8; ++i) m = fmaxf(m, fabsf(f[i]));
+    return m;
+}
+
+// Sec. 3.3.3 Eq. (2) / Sec. 4.1 Alg. 2, gather form: original slice at new position p.
+__device__ __host__ __forceinline__ uint64_t source_slice(uint64_t p, uint32_t X, uint32_t Y)
+{
+    const uint64_t T = (uint64_t)X * Y;
+    const uint64_t st = p / T, w = p % T;
+    const uint64_t j = w / Y, i = w % Y;
+    return st * T + i * X + j;
+}
+
+// ---------------------------------------------------------------------------
+// quantize (qwz_quantize, qgz_reorder): power-of-two block sizes
+// ---------------------------------------------------------------------------
+//
+// A wave owns a tile of 512*V consecutive elements of one output slice; load k of
+// lane l covers elements (k*64 + l)*8 .. +8, so every wave-wide load or store is
+// one contiguous run.  All V loads are issued before the first use.  Blocks of
+// >= 512 elements span B/512 loads (maximum folded across registers, then across
+// the wave); smaller blocks sit inside one load, B/8 lanes each.
+
+template <int DT, int BITS, int LOG2B, int V>
+__global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
+                                                       float* __restrict__ scales, uint64_t L,
+                                                       uint64_t tiles_per_slice, uint64_t total_tiles,
+                                                       uint32_t X, uint32_t Y)
+{
+    constexpr int B = 1 << LOG2B;
+    constexpr int TILE = 512 * V;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wid >= total_tiles) return;
+    const uint64_t p = wid / tiles_per_slice, t = wid % tiles_per_slice;
+    const uint64_t src = (X == 1 || Y == 1) ? p : source_slice(p, X, Y);
+    const uint64_t in_base = src * L + t * TILE;
+    const uint64_t out_base = p * L + t * TILE;
+    const uint64_t rem = L - t * TILE;  // elements of this slice from the tile start on (>= 1)
+
+    float f[V][8];
+    bool ok[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const uint32_t off = (uint32_t)(k * kWave + lane) * 8u;
+        ok[k] = off < rem;
+        if (ok[k]) {
+            load8<DT>(x, in_base + off, f[k]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) f[k][i] = 0.0f;
+        }
+    }
+
+    if constexpr (B >= 512) {
+        constexpr int LPB = B / 512 > 0 ? B / 512 : 1;  // loads per block
+        static_assert(B < 512 || V % LPB == 0, "tile must hold whole blocks");
+#pragma unroll
+        for (int b0 = 0; b0 < V; b0 += LPB) {
+            float a = absmax8(f[b0]);
+#pragma unroll
+            for (int k = 1; k < LPB; ++k) a = fmaxf(a, absmax8(f[b0 + k]));
+            a = group_max<kWave>(a);
+            float scale, inv;
+            block_scale<BITS>(a, scale, inv);
+            if (lane == 0 && ok[b0]) scales[(out_base + (uint64_t)b0 * 512) >> LOG2B] = scale;
+#pragma unroll
+            for (int k = 0; k < LPB; ++k) {
+                const uint32_t off = (uint32_t)((b0 + k) * kWave + lane) * 8u;
+                if (ok[b0 + k]) store_codes8<BITS>(codes, out_base + off, f[b0 + k], inv);
+            }
+        }
+    } else {
+        constexpr int G = B / 8 > 0 ? B / 8 : 1;  // lanes per block
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            float a = group_max<(G < kWave ? G : kWave)>(absmax8(f[k]));
+            float scale, inv;
+            block_scale<BITS>(a, scale, inv);
+            const uint32_t off = (uint32_t)(k * kWave + lane) * 8u;
+            if (ok[k]) {
+                if ((lane & (G - 1)) == 0) scales[(out_base + off) >> LOG2B] = scale;
+                store_codes8<BITS>(codes, out_base + off, f[k], inv);
+            }
+        }
+    }
+}
+
+// Any block size that is a multiple of 32 (not a power of two, or larger than the
+// tiled kernel handles): one wave per block, two passes over the block; the second
+// pass re-reads what the first pulled into cache.
+template <int DT, int BITS>
+__global__ __launch_bounds__(kThreads) void k_quantize_anyblock(const void* __restrict__ x,
+                                                                uint8_t* __restrict__ codes,
+                                                                float* __restrict__ scales, uint64_t L,
+                                                                uint32_t B, uint64_t total_blocks, uint32_t X,
+                                                                uint32_t Y)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t ob = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (ob >= total_blocks) return;
+    const uint64_t bps = L / B;
+    const uint64_t p = ob / bps, r = ob % bps;
+    const uint64_t src = (X == 1 || Y == 1) ? p : source_slice(p, X, Y);
+    const uint64_t in_base = src * L + r * B, out_base = ob * B;
+    float a = 0.0f;
+    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
+        float f[8];
+        load8<DT>(x, in_base + off, f);
+        a = fmaxf(a, absmax8(f));
+    }
+    a = group_max<kWave>(a);
+    float scale, inv;
+    block_scale<BITS>(a, scale, inv);
+    if (lane == 0) scales[ob] = scale;
+    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
+        float f[8];
+        load8<DT>(x, in_base + off, f);
+        store_codes8<BITS>(codes, out_base + off, f, inv);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// decode helpers
+// ---------------------------------------------------------------------------
+
+// signed code i (0..7) of a dword of eight two's-complement nibbles
+__device__ __forceinline__ float nibble_f32(uint32_t w, int i)
+{
+    return (float)((int32_t)(w << (28 - 4 * i)) >> 28);
+}
+// signed code i (0..3) of a dword of four two's-complement bytes
+__device__ __forceinline__ float byte_f32(uint32_t w, int i)
+{
+    return (float)((int32_t)(w << (24 - 8 * i)) >> 24);
+}
+
+// ---------------------------------------------------------------------------
+// qwz_dequantize
+// ---------------------------------------------------------------------------
+//
+// Lane l of a wave decodes 8 consecutive elements per step (8 B of int8 codes or
+// 4 B of int4 codes in, 16 B of 16-bit values out), V steps per wave with all
+// loads issued first.  The writes are two thirds of the traffic, so they get the
+// full-width contiguous stores.
+
+template <int ODT, int BITS, int V>
+__global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restrict__ codes,
+                                                         const float* __restrict__ scales,
+                                                         void* __restrict__ y, uint64_t n, uint32_t B,
+                                                         int log2b /* -1: not a power of two */)
+{
+    constexpr int TILE = 512 * V;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t base = wid * TILE;
+    if (base >= n) return;
+    const uint64_t rem = n - base;
+
+    uint32_t w[V][2];
+    float s[V];
+    bool ok[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const uint32_t off = (uint32_t)(k * kWave + lane) * 8u;
+        ok[k] = off < rem;
+        w[k][0] = w[k][1] = 0;
+        s[k] = 0.0f;
+        if (ok[k]) {
+            const uint64_t e = base + off;
+            if (BITS == 8) {
+                u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(codes + e));
+                w[k][0] = v.x;
+                w[k][1] = v.y;
+            } else {
+                w[k][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(codes + (e >> 1)));
+            }
+            const uint64_t blk = log2b >= 0 ? (e >> log2b) : (e / B);
+            s[k] = scales[blk];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        if (!ok[k]) continue;
+        float d[8];
+        if (BITS == 8) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                d[i] = byte_f32(w[k][0], i) * s[k];
+                d[4 + i] = byte_f32(w[k][1], i) * s[k];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) d[i] = nibble_f32(w[k][0], i) * s[k];
+        }
+        const uint64_t e = base + (uint32_t)(k * kWave + lane) * 8u;
+        if (ODT == ZPP_F32) {
+            f32x4* o = reinterpret_cast<f32x4*>(static_cast<float*>(y) + e);
+            f32x4 a = {d[0], d[1], d[2], d[3]}, b = {d[4], d[5], d[6], d[7]};
+            __builtin_nontemporal_store(a, o);
+            __builtin_nontemporal_store(b, o + 1);
+        } else {
+            u32x4 o;
+            o.x = narrow2<ODT>(d[0], d[1]);
+            o.y = narrow2<ODT>(d[2], d[3]);
+            o.z = narrow2<ODT>(d[4], d[5]);
+            o.w = narrow2<ODT>(d[6], d[7]);
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(y) + e));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// the two reduce stages
+// ---------------------------------------------------------------------------
+
+struct PeerTable {
+    const uint8_t* codes[ZPP_MAX_PEERS];
+    const float* scales[ZPP_MAX_PEERS];
+};
+
+// elements a lane holds per 16-byte vector of codes
+template <int BITS>
+struct EPL {
+    static constexpr int value = 128 / BITS;  // 32 nibbles or 16 bytes
+};
+
+// acc[i] += decode(code_i, s) for the EPL codes of one 16-byte vector, in place
+template <int BITS>
+__device__ __forceinline__ void accumulate(float (&acc)[EPL<BITS>::value], const u32x4 w, float s)
+{
+    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+    if (BITS == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[j * 8 + i] = acc[j * 8 + i] + nibble_f32(d[j], i) * s;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[j * 4 + i] = acc[j * 4 + i] + byte_f32(d[j], i) * s;
+    }
+}
+
+// Sum of the K peers' decoded values for the EPL elements starting at element e.
+// Peers are added in ascending order; loads of U peers are in flight together.
+template <int BITS, int U>
+__device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t e, uint64_t blk,
+                                             float (&acc)[EPL<BITS>::value])
+{
+#pragma unroll
+    for (int i = 0; i < EPL<BITS>::value; ++i) acc[i] = 0.0f;
+    const uint64_t byte_off = e * BITS / 8;
+    for (int k0 = 0; k0 < K; k0 += U) {
+        u32x4 w[U];
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (k0 + u < K) {
+                w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(P.codes[k0 + u] + byte_off));
+                s[u] = P.scales[k0 + u][blk];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (k0 + u < K) accumulate<BITS>(acc, w[u], s[u]);
+    }
+}
+
+// qgz_intra_reduce, power-of-two blocks with EPL <= B <= 64*EPL: a lane owns EPL
+// consecutive output elements, B/EPL lanes form a block.
+template <int BITS, int LOG2B>
+__global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, int K, uint64_t m,
+                                                           uint8_t* __restrict__ codes_out,
+                                                           float* __restrict__ scales_out)
+{
+    constexpr int E = EPL<BITS>::value;
+    constexpr int B = 1 << LOG2B;
+    constexpr int G = B / E;
+    static_assert(G >= 1 && G <= kWave, "block must fit a wave");
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t e = (wid * kWave + lane) * E;
+    const bool ok = e < m;  // m % B == 0 and B % E == 0: a lane is all in or all out
+    float acc[E];
+    if (ok) {
+        reduce_peers<BITS, 4>(P, K, e, e >> LOG2B, acc);
+    } else {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+    }
+    float a = fabsf(acc[0]);
+#pragma unroll
+    for (int i = 1; i < E; ++i) a = fmaxf(a, fabsf(acc[i]));
+    a = group_max<G>(a);
+    float scale, inv;
+    block_scale<BITS>(a, scale, inv);
+    if (!ok) return;
+    if ((lane & (G - 1)) == 0) scales_out[e >> LOG2B] = scale;
+    u32x4 o;
+    uint32_t od[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t v = 0;
+        if (BITS == 4) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v |= (code_bits(acc[j * 8 + i], inv) & 0xfu) << (4 * i);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v |= (code_bits(acc[j * 4 + i], inv) & 0xffu) << (8 * i);
+        }
+        od[j] = v;
+    }
+    o.x = od[0]; o.y = od[1]; o.z = od[2]; o.w = od[3];
+    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(codes_out + e * BITS / 8));
+}
+
+// qgz_intra_reduce for any other block size: one wave per block, the sums wait in
+// LDS between the maximum and the encode.
+template <int BITS>
+__global__ __launch_bounds__(kWave) void k_intra_reduce_anyblock(const PeerTable P, int K, uint32_t B,
+                                                                 uint8_t* __restrict__ codes_out,
+                                                                 float* __restrict__ scales_out)
+{
+    __shared__ float sums[4096];
+    const int lane = threadIdx.x;
+    const uint64_t blk = blockIdx.x;
+    const uint64_t base = blk * B;
+    float a = 0.0f;
+    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
+        float r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = 0.0f;
+        const uint64_t e = base + off;
+        for (int k = 0; k < K; ++k) {
+            const float s = P.scales[k][blk];
+            if (BITS == 4) {
+                const uint32_t w = *reinterpret_cast<const uint32_t*>(P.codes[k] + (e >> 1));
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = r[i] + nibble_f32(w, i) * s;
+            } else {
+                const u32x2 w = *reinterpret_cast<const u32x2*>(P.codes[k] + e);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    r[i] = r[i] + byte_f32(w.x, i) * s;
+                    r[4 + i] = r[4 + i] + byte_f32(w.y, i) * s;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sums[off + i] = r[i];
+        a = fmaxf(a, absmax8(r));
+    }
+    a = group_max<kWave>(a);
+    float scale, inv;
+    block_scale<BITS>(a, scale, inv);
+    if (lane == 0) scales_out[blk] = scale;
+    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
+        float r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = sums[off + i];  // written by this same lane
+        store_codes8<BITS>(codes_out, base + off, r, inv);
+    }
+}
+
+// qgz_inter_reduce: element-wise, the block only selects the scale.
+template <int BITS>
+__global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, int K, uint64_t m, uint32_t B,
+                                                           int log2b, float divisor, float* __restrict__ out)
+{
+    constexpr int E = EPL<BITS>::value;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t e = (wid * kWave + lane) * E;
+    if (e >= m) return;  // m % 32 == 0 and E divides 32
+    float acc[E];
+    reduce_peers<BITS, 4>(P, K, e, log2b >= 0 ? (e >> log2b) : (e / B), acc);
+    f32x4* o = reinterpret_cast<f32x4*>(out + e);
+#pragma unroll
+    for (int i = 0; i < E; i += 4) {
+        f32x4 v = {acc[i] / divisor, acc[i + 1] / divisor, acc[i + 2] / divisor, acc[i + 3] / divisor};
+        __builtin_nontemporal_store(v, o + i / 4);
+    }
+}
+
+// Plain device copy, 16 bytes per lane and step: the measured bandwidth ceiling
+// the kernels above are compared with.
+__global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                   uint64_t nvec)
+{
+    const uint64_t i0 = ((uint64_t)blockIdx.x * kThreads) * 4 + threadIdx.x;
+    u32x4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (i0 + (uint64_t)k * kThreads < nvec) v[k] = __builtin_nontemporal_load(src + i0 + (uint64_t)k * kThreads);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (i0 + (uint64_t)k * kThreads < nvec) __builtin_nontemporal_store(v[k], dst + i0 + (uint64_t)k * kThreads);
+}
+
+// ---------------------------------------------------------------------------
+// host side: argument checks and launches
+// ---------------------------------------------------------------------------
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+bool valid_dtype(int d) { return d == ZPP_F16 || d == ZPP_BF16 || d == ZPP_F32; }
+bool valid_bits(int b) { return b == 4 || b == 8; }
+bool valid_block(int b) { return b >= 32 && b <= 4096 && b % 32 == 0; }
+int log2_or_neg(uint32_t b) { return (b & (b - 1)) == 0 ? __builtin_ctz(b) : -1; }
+
+int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? ZPP_OK : ZPP_ELAUNCH;
+}
+
+constexpr uint64_t kMaxGrid = 0x7fffffffull;
+
+template <int DT, int BITS, int LOG2B>
+int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t L, uint64_t slices, uint32_t X,
+                          uint32_t Y, hipStream_t st)
+{
+    constexpr int V = (1 << LOG2B) > 2048 ? (1 << LOG2B) / 512 : 4;
+    const uint64_t tps = (L + 512 * V - 1) / (512 * V);
+    const uint64_t tiles = tps * slices;
+    const uint64_t grid = (tiles + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+    k_quantize<DT, BITS, LOG2B, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, tps, tiles, X, Y);
+    return launch_status();
+}
+
+template <int DT, int BITS>
+int launch_quantize(const void* x, uint8_t* codes, float* scales, uint64_t L, uint64_t slices, uint32_t B,
+                    uint32_t X, uint32_t Y, hipStream_t st)
+{
+    switch (log2_or_neg(B)) {
+    case 5: return launch_quantize_tiled<DT, BITS, 5>(x, codes, scales, L, slices, X, Y, st);
+    case 6: return launch_quantize_tiled<DT, BITS, 6>(x, codes, scales, L, slices, X, Y, st);
+    case 7: return launch_quantize_tiled<DT, BITS, 7>(x, codes, scales, L, slices, X, Y, st);
+    case 8: return launch_quantize_tiled<DT, BITS, 8>(x, codes, scales, L, slices, X, Y, st);
+    case 9: return launch_quantize_tiled<DT, BITS, 9>(x, codes, scales, L, slices, X, Y, st);
+    case 10: return launch_quantize_tiled<DT, BITS, 10>(x, codes, scales, L, slices, X, Y, st);
+    case 11: return launch_quantize_tiled<DT, BITS, 11>(x, codes, scales, L, slices, X, Y, st);
+    case 12: return launch_quantize_tiled<DT, BITS, 12>(x, codes, scales, L, slices, X, Y, st);
+    default: break;
+    }
+    const uint64_t blocks = L / B * slices;
+    const uint64_t grid = (blocks + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+    k_quantize_anyblock<DT, BITS><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, B, blocks, X, Y);
+    return launch_status();
+}
+
+int dispatch_quantize(const void* x, int dtype, int bits, uint8_t* codes, float* scales, uint64_t L,
+                      uint64_t slices, uint32_t B, uint32_t X, uint32_t Y, hipStream_t st)
+{
+#define ZPP_Q(DT, BITS) return launch_quantize<DT, BITS>(x, codes, scales, L, slices, B, X, Y, st)
+    if (bits == 8) {
+        if (dtype == ZPP_F16) ZPP_Q(ZPP_F16, 8);
+        if (dtype == ZPP_BF16) ZPP_Q(ZPP_BF16, 8);
+        ZPP_Q(ZPP_F32, 8);
+    } else {
+        if (dtype == ZPP_F16) ZPP_Q(ZPP_F16, 4);
+        if (dtype == ZPP_BF16) ZPP_Q(ZPP_BF16, 4);
+        ZPP_Q(ZPP_F32, 4);
+    }
+#undef ZPP_Q
+}
+
+template <int BITS>
+int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* codes_out, float* scales_out,
+                 hipStream_t st)
+{
+    constexpr int E = EPL<BITS>::value;
+    const int l2 = log2_or_neg(B);
+    const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
+    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid || m / B > kMaxGrid) return ZPP_EINVAL;
+#define ZPP_I(L2)                                                                                               \
+    case L2:                                                                                                    \
+        k_intra_reduce<BITS, L2><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out); \
+        return launch_status()
+    if (l2 >= 0 && (int)B >= E && (int)B <= kWave * E) {
+        switch (l2) {
+            ZPP_I(5);
+            ZPP_I(6);
+            ZPP_I(7);
+            ZPP_I(8);
+            ZPP_I(9);
+            ZPP_I(10);
+        default: break;
+        }
+        if (BITS == 4 && l2 == 11) {
+            k_intra_reduce<BITS, (BITS == 4 ? 11 : 10)><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out);
+            return launch_status();
+        }
+    }
+#undef ZPP_I
+    k_intra_reduce_anyblock<BITS><<<dim3((uint32_t)(m / B)), dim3(kWave), 0, st>>>(P, K, B, codes_out, scales_out);
+    return launch_status();
+}
+
+int fill_table(PeerTable& P, const void* const* codes_in, const float* const* scales_in, int K)
+{
+    if (!codes_in || !scales_in || K < 1 || K > ZPP_MAX_PEERS) return ZPP_EINVAL;
+    for (int k = 0; k < ZPP_MAX_PEERS; ++k) {
+        P.codes[k] = nullptr;
+        P.scales[k] = nullptr;
+    }
+    for (int k = 0; k < K; ++k) {
+        if (!codes_in[k] || !scales_in[k] || !aligned(codes_in[k], 16) || !aligned(scales_in[k], 4)) return ZPP_EINVAL;
+        P.codes[k] = static_cast<const uint8_t*>(codes_in[k]);
+        P.scales[k] = scales_in[k];
+    }
+    return ZPP_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------
+
+extern "C" {
+
+size_t zpp_codes_bytes(size_t n, int bits) { return valid_bits(bits) ? n / 8 * (size_t)bits + (n % 8) * (size_t)bits / 8 : 0; }
+
+size_t zpp_scales_count(size_t n, int block) { return block > 0 ? n / (size_t)block : 0; }
+
+const char* zpp_strerror(int code)
+{
+    switch (code) {
+    case ZPP_OK: return "ok";
+    case ZPP_EINVAL: return "invalid argument (null or misaligned pointer, size not a multiple of the block, value out of range)";
+    case ZPP_ELAUNCH: return "HIP runtime refused the kernel launch";
+    case ZPP_EUNSUPPORTED: return "combination not supported by this build";
+    default: return "unknown zpp error code";
+    }
+}
+
+long long zpp_reorder_source_slice(long long p, int X, int Y, int S)
+{
+    if (X < 1 || Y < 1 || S < 1 || p < 0 || p >= (long long)X * Y * S) return -1;
+    return (long long)source_slice((uint64_t)p, (uint32_t)X, (uint32_t)Y);
+}
+
+long long zpp_reorder_mapped_slice(long long pid, int X, int Y, int S)
+{
+    if (X < 1 || Y < 1 || S < 1 || pid < 0 || pid >= (long long)X * Y * S) return -1;
+    // inverse permutation: the same transpose with the roles of X and Y exchanged
+    return (long long)source_slice((uint64_t)pid, (uint32_t)Y, (uint32_t)X);
+}
+
+int qwz_quantize(const void* x, int dtype, size_t n, int block, int bits, void* codes, float* scales, void* stream)
+{
+    if (!valid_dtype(dtype) || !valid_bits(bits) || !valid_block(block) || n % (size_t)block != 0) return ZPP_EINVAL;
+    if (n == 0) return ZPP_OK;
+    if (!x || !codes || !scales || !aligned(x, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return ZPP_EINVAL;
+    return dispatch_quantize(x, dtype, bits, static_cast<uint8_t*>(codes), scales, n, 1, (uint32_t)block, 1, 1,
+                             static_cast<hipStream_t>(stream));
+}
+
+int qgz_reorder(const void* grad, int dtype, size_t n, int X, int Y, int S, int block, int bits, void* codes,
+                float* scales, void* stream)
+{
+    if (!valid_dtype(dtype) || !valid_bits(bits) || !valid_block(block)) return ZPP_EINVAL;
+    if (X < 1 || Y < 1 || S < 1 || X > 65535 || Y > 65535 || S > 65535) return ZPP_EINVAL;
+    const uint64_t slices = (uint64_t)X * Y * S;
+    if (n % (slices * (uint64_t)block) != 0) return ZPP_EINVAL;
+    if (n == 0) return ZPP_OK;
+    if (!grad || !codes || !scales || !aligned(grad, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return ZPP_EINVAL;
+    return dispatch_quantize(grad, dtype, bits, static_cast<uint8_t*>(codes), scales, n / slices, slices,
+                             (uint32_t)block, (uint32_t)X, (uint32_t)Y, static_cast<hipStream_t>(stream));
+}
+
+int qwz_dequantize(const void* codes, const float* scales, size_t n, int block, int bits, int out_dtype, void* y,
+                   void* stream)
+{
+    if (!valid_dtype(out_dtype) || !valid_bits(bits) || !valid_block(block) || n % (size_t)block != 0) return ZPP_EINVAL;
+    if (n == 0) return ZPP_OK;
+    if (!y || !codes || !scales || !aligned(y, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return ZPP_EINVAL;
+    constexpr int V = 4;
+    const uint64_t waves = (n + 512 * V - 1) / (512 * V);
+    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+    const uint8_t* c = static_cast<const uint8_t*>(codes);
+    const int l2 = log2_or_neg((uint32_t)block);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+#define ZPP_D(ODT, BITS) k_dequantize<ODT, BITS, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2)
+    if (bits == 8) {
+        if (out_dtype == ZPP_F16) ZPP_D(ZPP_F16, 8);
+        else if (out_dtype == ZPP_BF16) ZPP_D(ZPP_BF16, 8);
+        else ZPP_D(ZPP_F32, 8);
+    } else {
+        if (out_dtype == ZPP_F16) ZPP_D(ZPP_F16, 4);
+        else if (out_dtype == ZPP_BF16) ZPP_D(ZPP_BF16, 4);
+        else ZPP_D(ZPP_F32, 4);
+    }
+#undef ZPP_D
+    return launch_status();
+}
+
+int qgz_intra_reduce(const void* const* codes_in, const float* const* scales_in, int ranks, size_t m, int block,
+                     int bits, void* codes_out, float* scales_out, void* stream)
+{
+    if (!valid_bits(bits) || !valid_block(block) || m % (size_t)block != 0) return ZPP_EINVAL;
+    PeerTable P;
+    if (fill_table(P, codes_in, scales_in, ranks) != ZPP_OK) return ZPP_EINVAL;
+    if (m == 0) return ZPP_OK;
+    if (!codes_out || !scales_out || !aligned(codes_out, 16) || !aligned(scales_out, 4)) return ZPP_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (bits == 4) return launch_intra<4>(P, ranks, m, (uint32_t)block, static_cast<uint8_t*>(codes_out), scales_out, st);
+    return launch_intra<8>(P, ranks, m, (uint32_t)block, static_cast<uint8_t*>(codes_out), scales_out, st);
+}
+
+int qgz_inter_reduce(const void* const* codes_in, const float* const* scales_in, int nodes, size_t m, int block,
+                     int bits, float divisor, float* out, void* stream)
+{
+    if (!valid_bits(bits) || !valid_block(block) || m % (size_t)block != 0 || !(divisor > 0.0f)) return ZPP_EINVAL;
+    PeerTable P;
+    if (fill_table(P, codes_in, scales_in, nodes) != ZPP_OK) return ZPP_EINVAL;
+    if (m == 0) return ZPP_OK;
+    if (!out || !aligned(out, 16)) return ZPP_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int l2 = log2_or_neg((uint32_t)block);
+    const int E = bits == 4 ? 32 : 16;
+    const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
+    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+    if (bits == 4)
+        k_inter_reduce<4><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, out);
+    else
+        k_inter_reduce<8><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, out);
+    return launch_status();
+}
+
+// Measurement helper (not part of the paper's method): copy `bytes` (a multiple of
+// 16) from src to dst with the same access width the kernels use.
+int zpp_stream_copy(void* dst, const void* src, size_t bytes, void* stream)
+{
+    if (bytes % 16 != 0) return ZPP_EINVAL;
+    if (bytes == 0) return ZPP_OK;
+    if (!dst || !src || !aligned(dst, 16) || !aligned(src, 16)) return ZPP_EINVAL;
+    const uint64_t nvec = bytes / 16;
+    const uint64_t grid = (nvec + kThreads * 4 - 1) / (kThreads * 4);
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+    k_copy<<<dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
+    return launch_status();
+}
+
+}  // extern "C"

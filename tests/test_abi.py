@@ -1,0 +1,69 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol
+that include/zpp.h declares; the host-only helpers behave as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2306_10209_amd import binding as zpp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "zpp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+)?[A-Za-z_][\w\s\*]*?\b(\w+)\s*\([^;{]*\)\s*;", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_declares_the_five_operations():
+    names = declared_functions()
+    for want in ("qwz_quantize", "qwz_dequantize", "qgz_reorder", "qgz_intra_reduce", "qgz_inter_reduce"):
+        assert want in names
+    assert set(zpp.EXPORTS) == set(names)
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(zpp.LIB_PATH), "build the library first: python -m paper_2306_10209_amd.build"
+    lib = ctypes.CDLL(zpp.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_size_helpers():
+    assert zpp.codes_bytes(1 << 20, 8) == 1 << 20
+    assert zpp.codes_bytes(1 << 20, 4) == 1 << 19
+    assert zpp.codes_bytes(2250006528, 4) == 1125003264      # beyond 32 bits of elements
+    assert zpp.codes_bytes(64, 5) == 0
+    assert zpp.scales_count(1 << 20, 256) == 4096
+    assert zpp.scales_count(10, 0) == 0
+    assert b"invalid" in zpp.lib().zpp_strerror(-1)
+
+
+def test_reorder_helpers_follow_eq2(golden_dir):
+    for line in open(os.path.join(golden_dir, "reorder_examples.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        head, seq = line.split(":")
+        X, Y = map(int, head.split())
+        seq = list(map(int, seq.split()))
+        assert [zpp.reorder_source_slice(p, X, Y, 1) for p in range(X * Y)] == seq
+        for pid in range(X * Y):
+            assert seq[zpp.reorder_mapped_slice(pid, X, Y, 1)] == pid
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    """Bad sizes are rejected before anything touches the device."""
+    L = zpp.lib()
+    fake = ctypes.c_void_p(0x1000)
+    assert L.qwz_quantize(fake, 0, 100, 32, 8, fake, fake, None) == -1        # n % block
+    assert L.qwz_quantize(fake, 0, 128, 48, 8, fake, fake, None) == -1        # block % 32
+    assert L.qwz_quantize(fake, 3, 128, 32, 8, fake, fake, None) == -1        # dtype
+    assert L.qwz_quantize(None, 0, 128, 32, 8, fake, fake, None) == -1        # null
+    assert L.qwz_quantize(ctypes.c_void_p(0x1008), 0, 128, 32, 8, fake, fake, None) == -1   # alignment
+    assert L.qwz_dequantize(fake, fake, 128, 32, 3, 0, fake, None) == -1      # bits
+    assert L.qgz_reorder(fake, 0, 4096, 8, 3, 1, 256, 4, fake, fake, None) == -1
+    assert L.qgz_reorder(fake, 0, 0, 8, 3, 1, 256, 4, fake, fake, None) == 0  # empty: no-op
+    assert L.qwz_quantize(None, 0, 0, 32, 8, None, None, None) == 0

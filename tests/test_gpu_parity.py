@@ -1,0 +1,376 @@
+"""GPU parity: every entry point of the C-ABI library, called through the ctypes
+binding, against the CPU oracle on the same seeded inputs.  Integer codes, fp32
+scales, 16-bit decodes and fp32 reduced gradients must be bit-identical."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_10209_amd import binding as zpp
+from paper_2306_10209_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TORCH_DT = {oracle.F16: torch.float16, oracle.BF16: torch.bfloat16, oracle.F32: torch.float32}
+
+
+def host_bits(t):
+    return workloads.as_bits(t)
+
+
+def make_input(n, dtype, kind, seed):
+    tdt = TORCH_DT[dtype]
+    if kind == "weights":
+        return workloads.weights(n, seed=seed, dtype=tdt)
+    return workloads.gradients(n, seed=seed, dtype=tdt)
+
+
+def guarded(nbytes_or_numel, dtype):
+    """Device buffer with 64 guard elements on both sides, filled with a pattern."""
+    pad = 64
+    fill = {torch.uint8: 0xA5, torch.float32: -123.25, torch.float16: -77.5, torch.bfloat16: -77.5}[dtype]
+    full = torch.full((nbytes_or_numel + 2 * pad,), fill, dtype=dtype, device=DEV)
+    return full, full[pad:pad + nbytes_or_numel]
+
+
+def assert_guards_intact(full, n, dtype):
+    pad = 64
+    fill = {torch.uint8: 0xA5, torch.float32: -123.25, torch.float16: -77.5, torch.bfloat16: -77.5}[dtype]
+    ref = torch.full((pad,), fill, dtype=dtype, device=DEV)
+    assert torch.equal(full[:pad], ref) and torch.equal(full[pad + n:], ref), "write outside the output"
+
+
+def eq_bytes(dev_tensor, host_array):
+    got = dev_tensor.detach().cpu().contiguous()
+    if got.dtype in (torch.float16, torch.bfloat16):
+        got = got.view(torch.int16)
+    got = got.numpy().view(np.uint8).reshape(-1)
+    want = np.ascontiguousarray(host_array).view(np.uint8).reshape(-1)
+    if got.size != want.size:
+        return False
+    return np.array_equal(got, want)
+
+
+# ----------------------------------------------------------------------------
+# qwZ
+# ----------------------------------------------------------------------------
+
+QWZ_CASES = [
+    # dtype, bits, block, blocks (odd counts: several tiles and a ragged tail)
+    (oracle.F16, 8, 256, 4096),       # the small round-trip configuration: 4096 x 256 fp16
+    (oracle.BF16, 8, 2048, 77),
+    (oracle.F16, 4, 512, 133),
+    (oracle.F16, 8, 32, 1001),
+    (oracle.BF16, 4, 64, 517),
+    (oracle.F16, 8, 128, 333),
+    (oracle.BF16, 8, 1024, 35),
+    (oracle.F16, 4, 4096, 13),
+    (oracle.F16, 8, 96, 301),         # not a power of two: generic path
+    (oracle.BF16, 4, 3072, 7),
+    (oracle.F32, 8, 256, 65),
+    (oracle.F32, 4, 2048, 9),
+    (oracle.F16, 8, 2048, 1),
+    (oracle.F16, 4, 32, 1),
+]
+
+
+@pytest.mark.parametrize("dtype,bits,block,blocks", QWZ_CASES)
+def test_qwz_round_trip_bit_exact(dtype, bits, block, blocks):
+    n = block * blocks
+    kind = "weights" if bits == 8 else "grads"
+    x = make_input(n, dtype, kind, seed=block + bits)
+    xb = host_bits(x)
+    want_codes, want_scales = oracle.qwz_quantize(xb, dtype, block, bits)
+
+    cfull, codes = guarded(n * bits // 8, torch.uint8)
+    sfull, scales = guarded(n // block, torch.float32)
+    zpp.qwz_quantize(x.to(DEV), block, bits, codes=codes, scales=scales)
+    torch.cuda.synchronize()
+    assert eq_bytes(scales, want_scales), "scales differ"
+    assert eq_bytes(codes, want_codes), "codes differ"
+    assert_guards_intact(cfull, n * bits // 8, torch.uint8)
+    assert_guards_intact(sfull, n // block, torch.float32)
+
+    for odt in (dtype, oracle.F32):
+        want_y = oracle.qwz_dequantize(want_codes, want_scales, n, block, bits, odt)
+        yfull, y = guarded(n, TORCH_DT[odt])
+        zpp.qwz_dequantize(codes, scales, n, block, bits, out=y)
+        torch.cuda.synchronize()
+        assert eq_bytes(y, want_y), f"decode to dtype {odt} differs"
+        assert_guards_intact(yfull, n, TORCH_DT[odt])
+
+
+def test_qwz_shards_written_at_offsets_equal_whole_tensor():
+    """The simulated all-gather: P ranks quantize their shard straight into their
+    slot of the gather buffer; the result is the whole tensor's quantization."""
+    P, block, bits = 8, 2048, 8
+    n = P * block * 11
+    x = workloads.weights(n, seed=3, dtype=torch.bfloat16)
+    want_codes, want_scales = oracle.qwz_quantize(host_bits(x), oracle.BF16, block, bits)
+    xd = x.to(DEV)
+    codes = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    scales = torch.zeros(n // block, dtype=torch.float32, device=DEV)
+    sh, shb = n // P, n // P // block
+    for r in range(P):
+        zpp.qwz_quantize(xd[r * sh:(r + 1) * sh], block, bits, codes=codes[r * sh:(r + 1) * sh],
+                         scales=scales[r * shb:(r + 1) * shb])
+    y = zpp.qwz_dequantize(codes, scales, n, block, bits, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert eq_bytes(codes, want_codes) and eq_bytes(scales, want_scales)
+    assert eq_bytes(y, oracle.qwz_dequantize(want_codes, want_scales, n, block, bits, oracle.BF16))
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qwz_special_blocks(bits):
+    """All-zero, negative-zero, tiny, threshold, largest-fp16, subnormal and
+    exact-tie blocks."""
+    block = 256
+    qmax = (1 << (bits - 1)) - 1
+    rows = []
+    rows.append(np.zeros(block, dtype=np.float32))
+    rows.append(np.full(block, -0.0, dtype=np.float32))
+    r = np.zeros(block, dtype=np.float32); r[3] = 2.0 ** -101; rows.append(r)
+    r = np.zeros(block, dtype=np.float32); r[0] = 2.0 ** -100; r[1] = -2.0 ** -101; rows.append(r)
+    rows.append(np.linspace(-3e38, 3e38, block).astype(np.float32))
+    rows.append((np.arange(block) - 31.5).astype(np.float32) * np.float32(1e-42))      # fp32 subnormals
+    r = np.zeros(block, dtype=np.float32); r[0] = qmax * 4.0                              # exact ties
+    r[1:2 * qmax + 1] = (np.arange(-qmax, qmax) + 0.5) * 4.0
+    rows.append(r)
+    x32 = np.concatenate(rows)
+    codes_w, scales_w = oracle.qwz_quantize(x32, oracle.F32, block, bits)
+    codes, scales = zpp.qwz_quantize(torch.from_numpy(x32).to(DEV), block, bits)
+    y = zpp.qwz_dequantize(codes, scales, x32.size, block, bits, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert eq_bytes(scales, scales_w) and eq_bytes(codes, codes_w)
+    assert eq_bytes(y, oracle.qwz_dequantize(codes_w, scales_w, x32.size, block, bits, oracle.F32))
+
+    # fp16: largest finite values and subnormals
+    block = 64
+    h = np.zeros(4 * block, dtype=np.float16)
+    h[0], h[1], h[2] = 65504.0, -65504.0, 1.0
+    h[block:2 * block] = np.arange(block).astype(np.float16) * np.float16(2.0 ** -24)
+    h[2 * block + 5] = np.float16(2.0 ** -24)
+    hb = h.view(np.uint16)
+    cw, sw = oracle.qwz_quantize(hb, oracle.F16, block, bits)
+    c, s = zpp.qwz_quantize(torch.from_numpy(h).to(DEV), block, bits)
+    y = zpp.qwz_dequantize(c, s, h.size, block, bits, out_dtype=torch.float16)
+    torch.cuda.synchronize()
+    assert eq_bytes(s, sw) and eq_bytes(c, cw)
+    assert eq_bytes(y, oracle.qwz_dequantize(cw, sw, h.size, block, bits, oracle.F16))
+
+
+def test_decode_rounds_to_nearest_even_in_16_bits():
+    """Every int8 code against scales chosen so that products fall between
+    16-bit neighbours, including exact ties and the subnormal range."""
+    block = 256
+    codes_np = np.resize(np.arange(-127, 128, dtype=np.int8), block).view(np.uint8)
+    scales_list = [1.0, 1.0 / 3, 2.0 ** -14 / 127, 2.0 ** -24, 3 * 2.0 ** -26, 65504.0 / 127, 2.0 ** -120,
+                   1.0009765625, 0.007874016]
+    nb = len(scales_list)
+    codes = np.tile(codes_np, nb)
+    scales = np.array(scales_list, dtype=np.float32)
+    cd = torch.from_numpy(codes).to(DEV)
+    sd = torch.from_numpy(scales).to(DEV)
+    for odt in (oracle.F16, oracle.BF16, oracle.F32):
+        y = zpp.qwz_dequantize(cd, sd, block * nb, block, 8, out_dtype=TORCH_DT[odt])
+        torch.cuda.synchronize()
+        assert eq_bytes(y, oracle.qwz_dequantize(codes, scales, block * nb, block, 8, odt)), odt
+
+
+# ----------------------------------------------------------------------------
+# qgZ: reorder
+# ----------------------------------------------------------------------------
+
+REORDER_CASES = [
+    # X, Y, S, block, bits, blocks per slice
+    (2, 2, 1, 32, 4, 3),
+    (8, 6, 1, 512, 4, 5),
+    (8, 48, 1, 512, 4, 1),
+    (8, 64, 1, 512, 4, 2),
+    (4, 3, 2, 64, 8, 9),
+    (3, 5, 3, 96, 4, 4),
+    (8, 2, 1, 2048, 4, 3),
+    (1, 7, 1, 256, 4, 5),
+    (16, 1, 2, 128, 8, 3),
+]
+
+
+@pytest.mark.parametrize("X,Y,S,block,bits,bps", REORDER_CASES)
+def test_qgz_reorder_bit_exact(X, Y, S, block, bits, bps):
+    n = X * Y * S * block * bps
+    g = workloads.gradients(n, seed=X * 1000 + Y)
+    want_codes, want_scales = oracle.qgz_reorder(host_bits(g), oracle.F16, X, Y, S, block, bits)
+    cfull, codes = guarded(n * bits // 8, torch.uint8)
+    sfull, scales = guarded(n // block, torch.float32)
+    zpp.qgz_reorder(g.to(DEV), X, Y, S, block, bits, codes=codes, scales=scales)
+    torch.cuda.synchronize()
+    assert eq_bytes(scales, want_scales), "scales differ"
+    assert eq_bytes(codes, want_codes), "codes differ"
+    assert_guards_intact(cfull, n * bits // 8, torch.uint8)
+    assert_guards_intact(sfull, n // block, torch.float32)
+
+
+def test_reorder_index_helpers_match_oracle():
+    for X, Y, S in [(2, 2, 1), (8, 48, 1), (3, 5, 4)]:
+        for p in range(X * Y * S):
+            assert zpp.reorder_source_slice(p, X, Y, S) == oracle.reorder_source_slice(p, X, Y, S)
+            assert zpp.reorder_mapped_slice(p, X, Y, S) == oracle.reorder_mapped_slice(p, X, Y, S)
+        assert zpp.reorder_source_slice(X * Y * S, X, Y, S) == -1
+
+
+# ----------------------------------------------------------------------------
+# qgZ: the two reduce stages
+# ----------------------------------------------------------------------------
+
+def _peer_inputs(K, m, block, bits, seed):
+    host, dev = [], []
+    for k in range(K):
+        g = workloads.gradients(m, seed=seed, tensor_id=k)
+        c, s = oracle.qwz_quantize(host_bits(g), oracle.F16, block, bits)
+        host.append((c, s))
+        dev.append((torch.from_numpy(c).to(DEV), torch.from_numpy(s).to(DEV)))
+    return host, dev
+
+
+INTRA_CASES = [
+    # X, block, bits, blocks
+    (8, 512, 4, 37),
+    (8, 32, 4, 129),
+    (2, 64, 4, 65),
+    (5, 2048, 4, 3),
+    (8, 4096, 4, 3),      # larger than a wave's tile: generic path
+    (3, 96, 4, 50),       # not a power of two
+    (8, 512, 8, 9),
+    (4, 32, 8, 67),
+    (7, 2048, 8, 2),
+    (1, 256, 4, 11),
+    (64, 128, 4, 5),
+]
+
+
+@pytest.mark.parametrize("X,block,bits,blocks", INTRA_CASES)
+def test_qgz_intra_reduce_bit_exact(X, block, bits, blocks):
+    m = block * blocks
+    host, dev = _peer_inputs(X, m, block, bits, seed=X + block)
+    want_codes, want_scales = oracle.qgz_intra_reduce([h[0] for h in host], [h[1] for h in host], m, block, bits)
+    cfull, codes = guarded(m * bits // 8, torch.uint8)
+    sfull, scales = guarded(m // block, torch.float32)
+    zpp.qgz_intra_reduce([d[0] for d in dev], [d[1] for d in dev], m, block, bits, codes_out=codes, scales_out=scales)
+    torch.cuda.synchronize()
+    assert eq_bytes(scales, want_scales), "scales differ"
+    assert eq_bytes(codes, want_codes), "codes differ"
+    assert_guards_intact(cfull, m * bits // 8, torch.uint8)
+    assert_guards_intact(sfull, m // block, torch.float32)
+
+
+INTER_CASES = [
+    # Y, block, bits, blocks, divisor
+    (48, 512, 4, 21, 384.0),
+    (2, 32, 4, 131, 1.0),
+    (5, 96, 4, 33, 5.0),
+    (64, 2048, 4, 2, 512.0),
+    (6, 64, 8, 77, 48.0),
+    (1, 4096, 8, 3, 3.0),
+]
+
+
+@pytest.mark.parametrize("Y,block,bits,blocks,div", INTER_CASES)
+def test_qgz_inter_reduce_bit_exact(Y, block, bits, blocks, div):
+    m = block * blocks
+    host, dev = _peer_inputs(Y, m, block, bits, seed=Y + block)
+    want = oracle.qgz_inter_reduce([h[0] for h in host], [h[1] for h in host], m, block, bits, div)
+    ofull, out = guarded(m, torch.float32)
+    zpp.qgz_inter_reduce([d[0] for d in dev], [d[1] for d in dev], m, block, bits, div, out=out)
+    torch.cuda.synchronize()
+    assert eq_bytes(out, want)
+    assert_guards_intact(ofull, m, torch.float32)
+
+
+@pytest.mark.parametrize("X,Y,block", [(2, 2, 32), (8, 6, 512), (4, 3, 64)])
+def test_whole_qgz_path_on_simulated_ranks(X, Y, block):
+    """W = X*Y ranks as W device buffers; the all-to-alls are pointer offsets.
+    Every rank's final partition must equal the oracle's, bit for bit."""
+    W, bits = X * Y, 4
+    L = block * 3
+    n = W * L
+    m = n // X
+    grads = [workloads.gradients(n, seed=77, tensor_id=r) for r in range(W)]
+    # oracle side
+    o_first = [oracle.qgz_reorder(host_bits(g), oracle.F16, X, Y, 1, block, bits) for g in grads]
+    # GPU side
+    d_first = [zpp.qgz_reorder(g.to(DEV), X, Y, 1, block, bits) for g in grads]
+    cb, sb = m * bits // 8, m // block
+    o_second, d_second = {}, {}
+    for node in range(Y):
+        for j in range(X):
+            o_second[(node, j)] = oracle.qgz_intra_reduce(
+                [o_first[node * X + k][0][j * cb:(j + 1) * cb] for k in range(X)],
+                [o_first[node * X + k][1][j * sb:(j + 1) * sb] for k in range(X)], m, block, bits)
+            d_second[(node, j)] = zpp.qgz_intra_reduce(
+                [d_first[node * X + k][0][j * cb:(j + 1) * cb] for k in range(X)],
+                [d_first[node * X + k][1][j * sb:(j + 1) * sb] for k in range(X)], m, block, bits)
+    cl, sl = L * bits // 8, L // block
+    for node in range(Y):
+        for j in range(X):
+            want = oracle.qgz_inter_reduce(
+                [o_second[(i, j)][0][node * cl:(node + 1) * cl] for i in range(Y)],
+                [o_second[(i, j)][1][node * sl:(node + 1) * sl] for i in range(Y)], L, block, bits, float(W))
+            got = zpp.qgz_inter_reduce(
+                [d_second[(i, j)][0][node * cl:(node + 1) * cl] for i in range(Y)],
+                [d_second[(i, j)][1][node * sl:(node + 1) * sl] for i in range(Y)], L, block, bits, float(W))
+            torch.cuda.synchronize()
+            assert eq_bytes(got, want), (node, j)
+
+
+# ----------------------------------------------------------------------------
+# argument handling through the C ABI
+# ----------------------------------------------------------------------------
+
+def test_empty_inputs_are_no_ops():
+    e16 = torch.empty(0, dtype=torch.float16, device=DEV)
+    e8 = torch.empty(0, dtype=torch.uint8, device=DEV)
+    e32 = torch.empty(0, dtype=torch.float32, device=DEV)
+    zpp.qwz_quantize(e16, 256, 8, codes=e8, scales=e32)
+    zpp.qwz_dequantize(e8, e32, 0, 256, 8, out=e16)
+    zpp.qgz_reorder(e16, 8, 48, 1, 512, 4, codes=e8, scales=e32)
+    one = torch.zeros(16, dtype=torch.uint8, device=DEV)
+    onef = torch.zeros(4, dtype=torch.float32, device=DEV)
+    zpp.qgz_intra_reduce([one], [onef], 0, 512, 4, codes_out=e8, scales_out=e32)
+    zpp.qgz_inter_reduce([one], [onef], 0, 512, 4, 1.0, out=e32)
+    torch.cuda.synchronize()
+
+
+def test_invalid_arguments_return_einval_and_launch_nothing():
+    x = torch.zeros(4096, dtype=torch.float16, device=DEV)
+    codes = torch.full((4096,), 0xA5, dtype=torch.uint8, device=DEV)
+    scales = torch.full((128,), -1.0, dtype=torch.float32, device=DEV)
+    bad = [
+        lambda: zpp.qwz_quantize(x[:4000], 256, 8, codes=codes, scales=scales),      # n % block
+        lambda: zpp.qwz_quantize(x, 48, 8, codes=codes, scales=scales),              # block % 32
+        lambda: zpp.qwz_quantize(x, 8192, 8, codes=codes, scales=scales),            # block too large
+        lambda: zpp.qwz_quantize(x, 256, 5, codes=codes, scales=scales),             # bits
+        lambda: zpp.qwz_quantize(x[1:257], 256, 8, codes=codes, scales=scales),      # misaligned input
+        lambda: zpp.qwz_quantize(x, 256, 8, codes=codes[1:], scales=scales),         # misaligned output
+        lambda: zpp.qgz_reorder(x, 8, 3, 1, 256, 4, codes=codes, scales=scales),     # n % (X*Y*block)
+        lambda: zpp.qgz_reorder(x, 0, 2, 1, 256, 4, codes=codes, scales=scales),
+        lambda: zpp.qgz_inter_reduce([codes], [scales], 4096, 256, 4, 0.0),          # divisor
+        lambda: zpp.qgz_inter_reduce([codes] * 65, [scales] * 65, 4096, 256, 4, 1.0),  # too many peers
+        lambda: zpp.qgz_intra_reduce([], [], 4096, 256, 4),
+    ]
+    for f in bad:
+        with pytest.raises(zpp.ZppError):
+            f()
+    torch.cuda.synchronize()
+    assert bool((codes == 0xA5).all()) and bool((scales == -1.0).all())
+
+
+def test_results_do_not_depend_on_what_the_output_held_before():
+    n, block = 512 * 301, 512
+    g = workloads.gradients(n, seed=5).to(DEV)
+    a = zpp.qgz_reorder(g, 7, 43, 1, block, 4, codes=torch.zeros(n // 2, dtype=torch.uint8, device=DEV),
+                        scales=torch.zeros(n // block, dtype=torch.float32, device=DEV))
+    b = zpp.qgz_reorder(g, 7, 43, 1, block, 4, codes=torch.full((n // 2,), 255, dtype=torch.uint8, device=DEV),
+                        scales=torch.full((n // block,), float("nan"), dtype=torch.float32, device=DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
