@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the qwZ/qgZ kernel path on one MI355X.
+
+A "step" is one simulated training step of one GPU's share of a 40-layer,
+hidden-12288 GPT-style model under ZeRO++ with X = 8 GPUs per node and Y = 48
+nodes (Sec. 3 of the paper; the collectives themselves are not part of the step):
+
+  forward,  per layer:  qwz_dequantize of the gathered int8 weights (bf16 out)
+  backward, per layer:  qwz_dequantize again, then for the layer's fp16 gradient
+                        qgz_reorder (fused reorder + int4 quantize),
+                        qgz_intra_reduce (8 peers -> int4),
+                        qgz_inter_reduce (48 nodes -> fp32 average),
+                        and qwz_quantize of the rank's own updated weight shard.
+
+Inputs are seeded synthetic tensors resident in HBM before the timed region.
+Prints ONE JSON line; `value` is algorithmic bytes per second over the whole step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+METRIC = "effective HBM GB/s (and % of peak) per qwZ/qgZ kernel at 1 MI355X"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=40)
+    ap.add_argument("--hidden", type=int, default=12288)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-div", type=int, default=4,
+                    help="the CPU oracle is timed on 1/div of one layer")
+    return ap.parse_args()
+
+
+class Bytes:
+    """Algorithmic bytes each operation must move (codes + fp32 scales + payload)."""
+
+    @staticmethod
+    def quantize(n, B, bits, in_bytes=2):
+        return n * in_bytes + n * bits // 8 + 4 * (n // B)
+
+    @staticmethod
+    def dequantize(n, B, bits, out_bytes=2):
+        return n * bits // 8 + 4 * (n // B) + n * out_bytes
+
+    @staticmethod
+    def intra(m, B, bits, X):
+        return (X + 1) * (m * bits // 8 + 4 * (m // B))
+
+    @staticmethod
+    def inter(m, B, bits, Y):
+        return Y * (m * bits // 8 + 4 * (m // B)) + 4 * m
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the P ranks of the method are simulated as buffers on it; "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2306_10209_amd import binding as zpp, workloads
+
+    zpp.lib()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    X, Y, W = 8, 48, 384
+    WB, WBITS = 2048, 8           # weights: int8, block 2048
+    GB_, GBITS = 512, 4           # gradients: int4, block 512
+    n_L = workloads.layer_numel(args.hidden)
+    assert n_L % (X * Y * GB_) == 0 and (n_L // W) % WB == 0
+    m = n_L // X                  # intra-node stage output elements
+    L = n_L // W                  # inter-node stage output elements = own partition
+    layers = args.layers
+
+    # ---------------- setup (untimed): resident inputs ----------------
+    t0 = time.time()
+    w = workloads.weights(n_L, device=dev, tensor_id=1)
+    wcodes, wscales = zpp.qwz_quantize(w, WB, WBITS)
+    torch.cuda.synchronize()
+    wout = w                       # reuse the 3.6 GB buffer as the dequantize output
+    own = workloads.weights(L, device=dev, tensor_id=2)
+    own_codes = torch.empty(L, dtype=torch.uint8, device=dev)
+    own_scales = torch.empty(L // WB, dtype=torch.float32, device=dev)
+    grad = workloads.gradients(n_L, device=dev, tensor_id=3, tail_std=0.0)
+    gcodes = torch.empty(n_L // 2, dtype=torch.uint8, device=dev)
+    gscales = torch.empty(n_L // GB_, dtype=torch.float32, device=dev)
+    # peers' contributions to the intra-node stage (2 sets), already encoded
+    peer_sets = []
+    for s in range(2):
+        peers = []
+        for k in range(X - 1):
+            g = workloads.gradients(m, device=dev, tensor_id=100 + s * 16 + k, tail_std=0.0)
+            peers.append(zpp.qwz_quantize(g, GB_, GBITS))
+            torch.cuda.synchronize()
+            del g
+        peer_sets.append(peers)
+    icodes = torch.empty(m // 2, dtype=torch.uint8, device=dev)
+    iscales = torch.empty(m // GB_, dtype=torch.float32, device=dev)
+    # other nodes' contributions to the inter-node stage (8 sets, so they do not stay in cache)
+    node_sets = []
+    for s in range(8):
+        g = workloads.gradients((Y - 1) * L, device=dev, tensor_id=200 + s, tail_std=0.0)
+        c, sc = zpp.qwz_quantize(g, GB_, GBITS)
+        torch.cuda.synchronize()
+        del g
+        node_sets.append(([c[i * L // 2:(i + 1) * L // 2] for i in range(Y - 1)],
+                          [sc[i * L // GB_:(i + 1) * L // GB_] for i in range(Y - 1)]))
+    gout = torch.empty(L, dtype=torch.float32, device=dev)
+    setup_s = time.time() - t0
+
+    bytes_per = {
+        "qwz_dequantize": Bytes.dequantize(n_L, WB, WBITS),
+        "qwz_quantize": Bytes.quantize(L, WB, WBITS),
+        "qgz_reorder": Bytes.quantize(n_L, GB_, GBITS),
+        "qgz_intra_reduce": Bytes.intra(m, GB_, GBITS, X),
+        "qgz_inter_reduce": Bytes.inter(L, GB_, GBITS, Y),
+    }
+    calls_per_step = {"qwz_dequantize": 2 * layers, "qwz_quantize": layers, "qgz_reorder": layers,
+                      "qgz_intra_reduce": layers, "qgz_inter_reduce": layers}
+    step_bytes = sum(bytes_per[k] * calls_per_step[k] for k in bytes_per)
+
+    events = {k: [] for k in bytes_per}
+
+    def timed(name, fn, record):
+        if record:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            events[name].append((a, b))
+        else:
+            fn()
+
+    def step(record):
+        for _ in range(layers):                                   # forward
+            timed("qwz_dequantize", lambda: zpp.qwz_dequantize(wcodes, wscales, n_L, WB, WBITS, out=wout), record)
+        for l in reversed(range(layers)):                         # backward
+            timed("qwz_dequantize", lambda: zpp.qwz_dequantize(wcodes, wscales, n_L, WB, WBITS, out=wout), record)
+            timed("qgz_reorder", lambda: zpp.qgz_reorder(grad, X, Y, 1, GB_, GBITS, codes=gcodes, scales=gscales), record)
+            peers = peer_sets[l % 2]
+            cin = [gcodes[:m // 2]] + [p[0] for p in peers]
+            sin = [gscales[:m // GB_]] + [p[1] for p in peers]
+            timed("qgz_intra_reduce", lambda: zpp.qgz_intra_reduce(cin, sin, m, GB_, GBITS, codes_out=icodes, scales_out=iscales), record)
+            nc, ns = node_sets[l % 8]
+            cin2 = [icodes[:L // 2]] + nc
+            sin2 = [iscales[:L // GB_]] + ns
+            timed("qgz_inter_reduce", lambda: zpp.qgz_inter_reduce(cin2, sin2, L, GB_, GBITS, float(W), out=gout), record)
+            timed("qwz_quantize", lambda: zpp.qwz_quantize(own, WB, WBITS, codes=own_codes, scales=own_scales), record)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = step_bytes / (elapsed / args.steps) / 1e9
+
+    kernels = {}
+    for k, ev in events.items():
+        ms = [a.elapsed_time(b) for a, b in ev]
+        avg = sum(ms) / len(ms)
+        gbs = bytes_per[k] / (avg * 1e-3) / 1e9
+        kernels[k] = {"bytes": bytes_per[k], "avg_ms": round(avg, 5), "min_ms": round(min(ms), 5),
+                      "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                      "launches": len(ms)}
+
+    # measured copy ceiling: 2 GiB read + 2 GiB written per launch
+    src = grad.view(torch.uint8)[: 1 << 31]
+    dst = wout.view(torch.uint8)[: 1 << 31]
+    for _ in range(2):
+        zpp.stream_copy(dst, src)
+    ce = []
+    for _ in range(5):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        zpp.stream_copy(dst, src)
+        b.record()
+        ce.append((a, b))
+    torch.cuda.synchronize()
+    copy_ms = min(a.elapsed_time(b) for a, b in ce)
+    copy_gbs = 2 * (1 << 31) / (copy_ms * 1e-3) / 1e9
+
+    dom = "qwz_dequantize"
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dom, {}).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "algorithmic_bytes_per_launch": bytes_per[dom], "avg_launch_ms": kernels[dom]["avg_ms"],
+                "copy_ceiling_GBps": round(copy_gbs, 1)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(args, n_L, X, Y, W, WB, WBITS, GB_, GBITS)
+
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[4]: per-step kernel sequence, one GPU's share of a {layers}-layer "
+                               f"hidden-{args.hidden} GPT-style model (bf16 weights int8 block {WB}, fp16 grads "
+                               f"int4 block {GB_}, X={X}, Y={Y})",
+                   "layers": layers, "hidden": args.hidden, "elements_per_layer": n_L,
+                   "step_algorithmic_bytes": step_bytes, "calls_per_step": calls_per_step},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(args, n_L, X, Y, W, WB, WBITS, GB_, GBITS):
+    """The CPU oracle, as it stands, on 1/div of one layer pushed through the same
+    six calls a layer costs in a step (2 dequantize, reorder, intra, inter, quantize)."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2306_10209_amd import workloads
+
+    div = args.cpu_sample_div
+    n = n_L // div
+    assert n % (X * Y * GB_) == 0 and (n // W) % WB == 0
+    m, L = n // X, n // W
+    threads = oracle.set_threads(0)
+    gen = "cuda:0" if torch.cuda.is_available() else "cpu"     # drawing the numbers is not part of the baseline
+    w = workloads.as_bits(workloads.weights(n, device=gen, tensor_id=1))
+    wc, ws = oracle.qwz_quantize(w, oracle.BF16, WB, WBITS)
+    g = workloads.as_bits(workloads.gradients(n, device=gen, tensor_id=3, tail_std=0.0))
+    peers = [oracle.qwz_quantize(workloads.as_bits(workloads.gradients(m, device=gen, tensor_id=100 + k, tail_std=0.0)),
+                                 oracle.F16, GB_, GBITS) for k in range(X - 1)]
+    nodes = [oracle.qwz_quantize(workloads.as_bits(workloads.gradients(L, device=gen, tensor_id=200 + i, tail_std=0.0)),
+                                 oracle.F16, GB_, GBITS) for i in range(Y - 1)]
+    own = workloads.as_bits(workloads.weights(L, device=gen, tensor_id=2))
+    t0 = time.perf_counter()
+    oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
+    oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
+    gc, gs = oracle.qgz_reorder(g, oracle.F16, X, Y, 1, GB_, GBITS)
+    ic, isc = oracle.qgz_intra_reduce([gc[:m // 2]] + [p[0] for p in peers], [gs[:m // GB_]] + [p[1] for p in peers],
+                                      m, GB_, GBITS)
+    oracle.qgz_inter_reduce([ic[:L // 2]] + [c for c, _ in nodes], [isc[:L // GB_]] + [s for _, s in nodes],
+                            L, GB_, GBITS, float(W))
+    oracle.qwz_quantize(own, oracle.BF16, WB, WBITS)
+    dt = time.perf_counter() - t0
+    nbytes = (2 * Bytes.dequantize(n, WB, WBITS) + Bytes.quantize(n, GB_, GBITS) + Bytes.intra(m, GB_, GBITS, X)
+              + Bytes.inter(L, GB_, GBITS, Y) + Bytes.quantize(L, WB, WBITS))
+    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"1/{div} of one layer ({n} elements) through the six calls a layer costs per step "
+                      f"(= 1/{div * args.layers} of a step), {dt:.1f} s of wall time",
+            "seconds": round(dt, 2)}
+
+
+if __name__ == "__main__":
+    main()
