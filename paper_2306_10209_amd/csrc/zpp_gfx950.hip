@@ -20,6 +20,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// 16-byte loads a wave issues per tile before it starts computing (tuning knobs)
+#ifndef ZPP_QUANT_V
+#define ZPP_QUANT_V 4
+#endif
+#ifndef ZPP_DEQ_V
+#define ZPP_DEQ_V 4
+#endif
+
 constexpr int kWave = 64;
 constexpr int kWavesPerWG = 4;
 constexpr int kThreads = kWave * kWavesPerWG;
@@ -394,16 +402,53 @@ struct EPL {
     static constexpr int value = 128 / BITS;  // 32 nibbles or 16 bytes
 };
 
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// acc[0..8) += decode(nibble_i of w, s), i = 0..7 (nibble i = bits 4i..4i+3).
+//
+// decode is float(q)*s with one rounding.  It is computed as a single fused
+// multiply-add whose multiplicand is read straight from the code word: after
+// flipping each nibble's top bit the nibble holds u = q + 8, and a 16-bit lane
+// whose only set bits are such a nibble is, read as binary16, the subnormal
+// u*2^-24 (bits 0-3) or u*2^-20 (bits 4-7).  fma(u*2^-24, s*2^24, -8*s) is the
+// exact value (u-8)*s = q*s rounded once, because s*2^24, s*2^20 and 8*s are exact
+// (power-of-two factors, s < 2^100 checked by the caller).  The conversion of the
+// binary16 operand happens inside the mixed-precision fma instruction.
+__device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w, float s_lo, float s_hi,
+                                             float bias)
+{
+    const uint32_t u = w ^ 0x88888888u;
+    const uint32_t v = u >> 8;
+    const f16x2 a = __builtin_bit_cast(f16x2, u & 0x000F000Fu);  // elements 0, 4
+    const f16x2 b = __builtin_bit_cast(f16x2, u & 0x00F000F0u);  // elements 1, 5
+    const f16x2 c = __builtin_bit_cast(f16x2, v & 0x000F000Fu);  // elements 2, 6
+    const f16x2 d = __builtin_bit_cast(f16x2, v & 0x00F000F0u);  // elements 3, 7
+    acc[0] = acc[0] + __builtin_fmaf((float)a.x, s_lo, bias);
+    acc[1] = acc[1] + __builtin_fmaf((float)b.x, s_hi, bias);
+    acc[2] = acc[2] + __builtin_fmaf((float)c.x, s_lo, bias);
+    acc[3] = acc[3] + __builtin_fmaf((float)d.x, s_hi, bias);
+    acc[4] = acc[4] + __builtin_fmaf((float)a.y, s_lo, bias);
+    acc[5] = acc[5] + __builtin_fmaf((float)b.y, s_hi, bias);
+    acc[6] = acc[6] + __builtin_fmaf((float)c.y, s_lo, bias);
+    acc[7] = acc[7] + __builtin_fmaf((float)d.y, s_hi, bias);
+}
+
 // acc[i] += decode(code_i, s) for the EPL codes of one 16-byte vector, in place
 template <int BITS>
 __device__ __forceinline__ void accumulate(float (&acc)[EPL<BITS>::value], const u32x4 w, float s)
 {
     const uint32_t d[4] = {w.x, w.y, w.z, w.w};
     if (BITS == 4) {
+        if (s < 0x1p100f) {
+            const float s_lo = s * 0x1p24f, s_hi = s * 0x1p20f, bias = s * -8.0f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j) add_nibbles8(acc + j * 8, d[j], s_lo, s_hi, bias);
+        } else {  // scales this large never come from 16-bit gradients; plain convert and multiply
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[j * 8 + i] = acc[j * 8 + i] + nibble_f32(d[j], i) * s;
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[j * 8 + i] = acc[j * 8 + i] + nibble_f32(d[j], i) * s;
+        }
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -412,8 +457,27 @@ __device__ __forceinline__ void accumulate(float (&acc)[EPL<BITS>::value], const
     }
 }
 
+template <int U>
+__device__ __forceinline__ void load_group(const PeerTable& P, int k0, uint64_t byte_off, uint64_t blk,
+                                           u32x4 (&w)[U], float (&s)[U])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(P.codes[k0 + u] + byte_off));
+        s[u] = P.scales[k0 + u][blk];
+    }
+}
+
+template <int BITS, int U>
+__device__ __forceinline__ void add_group(float (&acc)[EPL<BITS>::value], const u32x4 (&w)[U], const float (&s)[U])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) accumulate<BITS>(acc, w[u], s[u]);
+}
+
 // Sum of the K peers' decoded values for the EPL elements starting at element e.
-// Peers are added in ascending order; loads of U peers are in flight together.
+// Peers are added in ascending order.  They are fetched in groups of U; the next
+// group's loads are issued before the current group is decoded.
 template <int BITS, int U>
 __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t e, uint64_t blk,
                                              float (&acc)[EPL<BITS>::value])
@@ -421,19 +485,23 @@ __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t
 #pragma unroll
     for (int i = 0; i < EPL<BITS>::value; ++i) acc[i] = 0.0f;
     const uint64_t byte_off = e * BITS / 8;
-    for (int k0 = 0; k0 < K; k0 += U) {
-        u32x4 w[U];
-        float s[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (k0 + u < K) {
-                w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(P.codes[k0 + u] + byte_off));
-                s[u] = P.scales[k0 + u][blk];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (k0 + u < K) accumulate<BITS>(acc, w[u], s[u]);
+    const int full = K / U;
+    u32x4 wa[U], wb[U];
+    float sa[U], sb[U];
+    if (full > 0) load_group<U>(P, 0, byte_off, blk, wa, sa);
+    int g = 0;
+    for (; g + 2 <= full; g += 2) {
+        load_group<U>(P, (g + 1) * U, byte_off, blk, wb, sb);
+        add_group<BITS, U>(acc, wa, sa);
+        if (g + 2 < full) load_group<U>(P, (g + 2) * U, byte_off, blk, wa, sa);
+        add_group<BITS, U>(acc, wb, sb);
+    }
+    if (g < full) add_group<BITS, U>(acc, wa, sa);
+    for (int k = full * U; k < K; ++k) {
+        u32x4 w1[1];
+        float s1[1];
+        load_group<1>(P, k, byte_off, blk, w1, s1);
+        add_group<BITS, 1>(acc, w1, s1);
     }
 }
 
@@ -533,23 +601,51 @@ __global__ __launch_bounds__(kWave) void k_intra_reduce_anyblock(const PeerTable
     }
 }
 
-// qgz_inter_reduce: element-wise, the block only selects the scale.
+// qgz_inter_reduce: element-wise, the block only selects the scale.  A lane sums
+// the EPL consecutive elements of its 16-byte code vectors; the wave then turns
+// its 64 x EPL results through LDS so that each store instruction writes one
+// contiguous run of 1 KB (lane l, store j: floats 4*(64j + l) .. +4 of the tile).
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, int K, uint64_t m, uint32_t B,
                                                            int log2b, float divisor, float* __restrict__ out)
 {
     constexpr int E = EPL<BITS>::value;
+    constexpr int CH = E / 4;  // 16-byte chunks of results per lane
+    __shared__ f32x4 turn[kWavesPerWG][kWave * CH];
     const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t e = (wid * kWave + lane) * E;
-    if (e >= m) return;  // m % 32 == 0 and E divides 32
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + wave;
+    const uint64_t tile = wid * kWave * E;
+    if (tile >= m) return;
+    const uint64_t e = tile + (uint64_t)lane * E;
+    const bool ok = e < m;  // m % 32 == 0 and E divides 32: a lane is all in or all out
     float acc[E];
-    reduce_peers<BITS, 4>(P, K, e, log2b >= 0 ? (e >> log2b) : (e / B), acc);
-    f32x4* o = reinterpret_cast<f32x4*>(out + e);
+    if (ok) {
+        reduce_peers<BITS, 4>(P, K, e, log2b >= 0 ? (e >> log2b) : (e / B), acc);
+    } else {
 #pragma unroll
-    for (int i = 0; i < E; i += 4) {
-        f32x4 v = {acc[i] / divisor, acc[i + 1] / divisor, acc[i + 2] / divisor, acc[i + 3] / divisor};
-        __builtin_nontemporal_store(v, o + i / 4);
+        for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+    }
+    f32x4* mine = turn[wave];
+    // chunk i of lane l is parked in row l at column i ^ (l % CH): rows are read back
+    // whole, and lanes writing the same chunk index spread over the columns
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        f32x4 v = {acc[4 * i] / divisor, acc[4 * i + 1] / divisor, acc[4 * i + 2] / divisor,
+                   acc[4 * i + 3] / divisor};
+        mine[lane * CH + (i ^ (lane & (CH - 1)))] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    f32x4* o = reinterpret_cast<f32x4*>(out + tile);
+    const uint64_t chunks = (m - tile) / 4;  // 16-byte chunks of this tile that exist
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const uint32_t c = (uint32_t)j * kWave + lane;  // chunk of the tile this lane stores now
+        const uint32_t src_lane = c / CH, src_i = c % CH;
+        const f32x4 v = mine[src_lane * CH + (src_i ^ (src_lane & (CH - 1)))];
+        if (c < chunks) __builtin_nontemporal_store(v, o + c);
     }
 }
 
@@ -589,7 +685,7 @@ template <int DT, int BITS, int LOG2B>
 int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t L, uint64_t slices, uint32_t X,
                           uint32_t Y, hipStream_t st)
 {
-    constexpr int V = (1 << LOG2B) > 2048 ? (1 << LOG2B) / 512 : 4;
+    constexpr int V = (1 << LOG2B) / 512 > ZPP_QUANT_V ? (1 << LOG2B) / 512 : ZPP_QUANT_V;
     const uint64_t tps = (L + 512 * V - 1) / (512 * V);
     const uint64_t tiles = tps * slices;
     const uint64_t grid = (tiles + kWavesPerWG - 1) / kWavesPerWG;
@@ -748,7 +844,7 @@ int qwz_dequantize(const void* codes, const float* scales, size_t n, int block, 
     if (!valid_dtype(out_dtype) || !valid_bits(bits) || !valid_block(block) || n % (size_t)block != 0) return ZPP_EINVAL;
     if (n == 0) return ZPP_OK;
     if (!y || !codes || !scales || !aligned(y, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return ZPP_EINVAL;
-    constexpr int V = 4;
+    constexpr int V = ZPP_DEQ_V;
     const uint64_t waves = (n + 512 * V - 1) / (512 * V);
     const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
     if (grid > kMaxGrid) return ZPP_EINVAL;
