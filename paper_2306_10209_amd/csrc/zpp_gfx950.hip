@@ -10,6 +10,7 @@
 // explicitly and computes a single correctly rounded product (the addend only
 // removes a bias exactly), so results stay bit-identical to the plain formulas.
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "zpp.h"
@@ -25,7 +26,18 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define ZPP_QUANT_V 4
 #endif
 #ifndef ZPP_DEQ_V
-#define ZPP_DEQ_V 4
+#define ZPP_DEQ_V 2
+#endif
+// reduce stages: peers fetched per group, and whether the next group is fetched ahead
+#ifndef ZPP_RED_U
+#define ZPP_RED_U 4
+#endif
+#ifndef ZPP_RED_PREFETCH
+#define ZPP_RED_PREFETCH true
+#endif
+// reduce stages: fewest waves for which a lane takes the widest code vector
+#ifndef ZPP_RED_MIN_WAVES
+#define ZPP_RED_MIN_WAVES 8192
 #endif
 
 constexpr int kWave = 64;
@@ -396,11 +408,25 @@ struct PeerTable {
     const float* scales[ZPP_MAX_PEERS];
 };
 
-// elements a lane holds per 16-byte vector of codes
-template <int BITS>
+// elements a lane holds per vector of NW code dwords (NW = 1, 2 or 4)
+template <int BITS, int NW = 4>
 struct EPL {
-    static constexpr int value = 128 / BITS;  // 32 nibbles or 16 bytes
+    static constexpr int value = NW * 32 / BITS;
 };
+
+template <int NW>
+__device__ __forceinline__ void load_words(const uint8_t* __restrict__ p, uint32_t (&w)[NW])
+{
+    if constexpr (NW == 4) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    } else if constexpr (NW == 2) {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+        w[0] = v.x; w[1] = v.y;
+    } else {
+        w[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+    }
+}
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
@@ -433,75 +459,84 @@ __device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w
     acc[7] = acc[7] + __builtin_fmaf((float)d.y, s_hi, bias);
 }
 
-// acc[i] += decode(code_i, s) for the EPL codes of one 16-byte vector, in place
-template <int BITS>
-__device__ __forceinline__ void accumulate(float (&acc)[EPL<BITS>::value], const u32x4 w, float s)
+// acc[i] += decode(code_i, s) for the codes of NW dwords, in place
+template <int BITS, int NW>
+__device__ __forceinline__ void accumulate(float (&acc)[(EPL<BITS, NW>::value)], const uint32_t (&d)[NW], float s)
 {
-    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
     if (BITS == 4) {
         if (s < 0x1p100f) {
             const float s_lo = s * 0x1p24f, s_hi = s * 0x1p20f, bias = s * -8.0f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) add_nibbles8(acc + j * 8, d[j], s_lo, s_hi, bias);
+            for (int j = 0; j < NW; ++j) add_nibbles8(acc + j * 8, d[j], s_lo, s_hi, bias);
         } else {  // scales this large never come from 16-bit gradients; plain convert and multiply
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NW; ++j)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc[j * 8 + i] = acc[j * 8 + i] + nibble_f32(d[j], i) * s;
         }
     } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NW; ++j)
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[j * 4 + i] = acc[j * 4 + i] + byte_f32(d[j], i) * s;
     }
 }
 
-template <int U>
+template <int NW, int U>
 __device__ __forceinline__ void load_group(const PeerTable& P, int k0, uint64_t byte_off, uint64_t blk,
-                                           u32x4 (&w)[U], float (&s)[U])
+                                           uint32_t (&w)[U][NW], float (&s)[U])
 {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(P.codes[k0 + u] + byte_off));
+        load_words<NW>(P.codes[k0 + u] + byte_off, w[u]);
         s[u] = P.scales[k0 + u][blk];
     }
 }
 
-template <int BITS, int U>
-__device__ __forceinline__ void add_group(float (&acc)[EPL<BITS>::value], const u32x4 (&w)[U], const float (&s)[U])
+template <int BITS, int NW, int U>
+__device__ __forceinline__ void add_group(float (&acc)[(EPL<BITS, NW>::value)], const uint32_t (&w)[U][NW],
+                                          const float (&s)[U])
 {
 #pragma unroll
-    for (int u = 0; u < U; ++u) accumulate<BITS>(acc, w[u], s[u]);
+    for (int u = 0; u < U; ++u) accumulate<BITS, NW>(acc, w[u], s[u]);
 }
 
 // Sum of the K peers' decoded values for the EPL elements starting at element e.
-// Peers are added in ascending order.  They are fetched in groups of U; the next
-// group's loads are issued before the current group is decoded.
-template <int BITS, int U>
+// Peers are added in ascending order.  They are fetched in groups of U; with
+// PREFETCH the next group's loads are issued before the current group is decoded.
+template <int BITS, int NW, int U, bool PREFETCH>
 __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t e, uint64_t blk,
-                                             float (&acc)[EPL<BITS>::value])
+                                             float (&acc)[(EPL<BITS, NW>::value)])
 {
 #pragma unroll
-    for (int i = 0; i < EPL<BITS>::value; ++i) acc[i] = 0.0f;
+    for (int i = 0; i < EPL<BITS, NW>::value; ++i) acc[i] = 0.0f;
     const uint64_t byte_off = e * BITS / 8;
     const int full = K / U;
-    u32x4 wa[U], wb[U];
-    float sa[U], sb[U];
-    if (full > 0) load_group<U>(P, 0, byte_off, blk, wa, sa);
-    int g = 0;
-    for (; g + 2 <= full; g += 2) {
-        load_group<U>(P, (g + 1) * U, byte_off, blk, wb, sb);
-        add_group<BITS, U>(acc, wa, sa);
-        if (g + 2 < full) load_group<U>(P, (g + 2) * U, byte_off, blk, wa, sa);
-        add_group<BITS, U>(acc, wb, sb);
+    if constexpr (PREFETCH) {
+        uint32_t wa[U][NW], wb[U][NW];
+        float sa[U], sb[U];
+        if (full > 0) load_group<NW, U>(P, 0, byte_off, blk, wa, sa);
+        int g = 0;
+        for (; g + 2 <= full; g += 2) {
+            load_group<NW, U>(P, (g + 1) * U, byte_off, blk, wb, sb);
+            add_group<BITS, NW, U>(acc, wa, sa);
+            if (g + 2 < full) load_group<NW, U>(P, (g + 2) * U, byte_off, blk, wa, sa);
+            add_group<BITS, NW, U>(acc, wb, sb);
+        }
+        if (g < full) add_group<BITS, NW, U>(acc, wa, sa);
+    } else {
+        for (int g = 0; g < full; ++g) {
+            uint32_t w[U][NW];
+            float sc[U];
+            load_group<NW, U>(P, g * U, byte_off, blk, w, sc);
+            add_group<BITS, NW, U>(acc, w, sc);
+        }
     }
-    if (g < full) add_group<BITS, U>(acc, wa, sa);
     for (int k = full * U; k < K; ++k) {
-        u32x4 w1[1];
+        uint32_t w1[1][NW];
         float s1[1];
-        load_group<1>(P, k, byte_off, blk, w1, s1);
-        add_group<BITS, 1>(acc, w1, s1);
+        load_group<NW, 1>(P, k, byte_off, blk, w1, s1);
+        add_group<BITS, NW, 1>(acc, w1, s1);
     }
 }
 
@@ -522,7 +557,7 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
     const bool ok = e < m;  // m % B == 0 and B % E == 0: a lane is all in or all out
     float acc[E];
     if (ok) {
-        reduce_peers<BITS, 4>(P, K, e, e >> LOG2B, acc);
+        reduce_peers<BITS, 4, ZPP_RED_U, ZPP_RED_PREFETCH>(P, K, e, e >> LOG2B, acc);
     } else {
 #pragma unroll
         for (int i = 0; i < E; ++i) acc[i] = 0.0f;
@@ -605,11 +640,11 @@ __global__ __launch_bounds__(kWave) void k_intra_reduce_anyblock(const PeerTable
 // the EPL consecutive elements of its 16-byte code vectors; the wave then turns
 // its 64 x EPL results through LDS so that each store instruction writes one
 // contiguous run of 1 KB (lane l, store j: floats 4*(64j + l) .. +4 of the tile).
-template <int BITS>
+template <int BITS, int NW>
 __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, int K, uint64_t m, uint32_t B,
-                                                           int log2b, float divisor, float* __restrict__ out)
+                                                           int log2b, float divisor, float recip, float* __restrict__ out)
 {
-    constexpr int E = EPL<BITS>::value;
+    constexpr int E = EPL<BITS, NW>::value;
     constexpr int CH = E / 4;  // 16-byte chunks of results per lane
     __shared__ f32x4 turn[kWavesPerWG][kWave * CH];
     const int lane = threadIdx.x & (kWave - 1);
@@ -621,7 +656,7 @@ __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, in
     const bool ok = e < m;  // m % 32 == 0 and E divides 32: a lane is all in or all out
     float acc[E];
     if (ok) {
-        reduce_peers<BITS, 4>(P, K, e, log2b >= 0 ? (e >> log2b) : (e / B), acc);
+        reduce_peers<BITS, NW, ZPP_RED_U, ZPP_RED_PREFETCH>(P, K, e, log2b >= 0 ? (e >> log2b) : (e / B), acc);
     } else {
 #pragma unroll
         for (int i = 0; i < E; ++i) acc[i] = 0.0f;
@@ -629,10 +664,17 @@ __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, in
     f32x4* mine = turn[wave];
     // chunk i of lane l is parked in row l at column i ^ (l % CH): rows are read back
     // whole, and lanes writing the same chunk index spread over the columns
+    // a power-of-two divisor: multiplying by its (exact) reciprocal rounds the same real number
+    if (recip != 0.0f) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = acc[i] * recip;
+    } else {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = acc[i] / divisor;
+    }
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-        f32x4 v = {acc[4 * i] / divisor, acc[4 * i + 1] / divisor, acc[4 * i + 2] / divisor,
-                   acc[4 * i + 3] / divisor};
+        f32x4 v = {acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
         mine[lane * CH + (i ^ (lane & (CH - 1)))] = v;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -888,14 +930,27 @@ int qgz_inter_reduce(const void* const* codes_in, const float* const* scales_in,
     if (!out || !aligned(out, 16)) return ZPP_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int l2 = log2_or_neg((uint32_t)block);
-    const int E = bits == 4 ? 32 : 16;
-    const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
+    int dexp = 0;
+    const float recip = (frexpf(divisor, &dexp) == 0.5f && dexp >= -125) ? 1.0f / divisor : 0.0f;
+    // widest code vector per lane that still leaves enough waves to fill the chip
+    const int per_dword = 32 / bits;
+    int nw = 4;
+    while (nw > 1 && (m + (uint64_t)kWave * nw * per_dword - 1) / ((uint64_t)kWave * nw * per_dword) < ZPP_RED_MIN_WAVES) nw >>= 1;
+    const uint64_t per_wave = (uint64_t)kWave * nw * per_dword;
+    const uint64_t waves = (m + per_wave - 1) / per_wave;
     const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
     if (grid > kMaxGrid) return ZPP_EINVAL;
-    if (bits == 4)
-        k_inter_reduce<4><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, out);
-    else
-        k_inter_reduce<8><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, out);
+#define ZPP_R(BITS, NW) k_inter_reduce<BITS, NW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, recip, out)
+    if (bits == 4) {
+        if (nw == 4) ZPP_R(4, 4);
+        else if (nw == 2) ZPP_R(4, 2);
+        else ZPP_R(4, 1);
+    } else {
+        if (nw == 4) ZPP_R(8, 4);
+        else if (nw == 2) ZPP_R(8, 2);
+        else ZPP_R(8, 1);
+    }
+#undef ZPP_R
     return launch_status();
 }
 
