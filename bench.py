@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=40)
     ap.add_argument("--hidden", type=int, default=12288)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the per-kernel timings at the shapes of the other configurations")
     ap.add_argument("--cpu-sample-div", type=int, default=4,
                     help="the CPU oracle is timed on 1/div of one layer")
     return ap.parse_args()
@@ -212,6 +214,10 @@ def main():
                 "algorithmic_bytes_per_launch": bytes_per[dom], "avg_launch_ms": kernels[dom]["avg_ms"],
                 "copy_ceiling_GBps": round(copy_gbs, 1)}
 
+    del w, wout, grad, gcodes, gscales, peer_sets, node_sets, wcodes, src, dst
+    torch.cuda.empty_cache()
+    per_config = None if args.no_configs else per_config_kernels(torch, zpp, workloads, dev)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(args, n_L, X, Y, W, WB, WBITS, GB_, GBITS)
@@ -226,9 +232,114 @@ def main():
                    "layers": layers, "hidden": args.hidden, "elements_per_layer": n_L,
                    "step_algorithmic_bytes": step_bytes, "calls_per_step": calls_per_step},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "setup_s": round(setup_s, 1),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "other_configs": per_config,
+        "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))
+
+
+def per_config_kernels(torch, zpp, workloads, dev):
+    """Each kernel alone at the shapes of configs[0..3]: median of 20 launches after 3
+    warm-ups, HIP events on the launch stream.  GB/s of algorithmic bytes."""
+    res = {}
+
+    def run(name, nbytes, fn, note=None):
+        for _ in range(3):
+            fn()
+        ev = []
+        for _ in range(20):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        med = ms[len(ms) // 2]
+        gbs = nbytes / (med * 1e-3) / 1e9
+        res[name] = {"bytes": int(nbytes), "median_us": round(med * 1e3, 2), "min_us": round(ms[0] * 1e3, 2),
+                     "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        if note:
+            res[name]["note"] = note
+
+    # configs[0]: one fp16 4096x256 tensor, int8 block 256 (3 MB: launch-latency bound, cache resident)
+    n = 1 << 20
+    x = workloads.weights(n, device=dev, tensor_id=30, dtype=torch.float16, outlier_prob=0.0)
+    c, s = zpp.qwz_quantize(x, 256, 8)
+    note = "3 MB per launch: bounded by launch latency, resident in cache; parity configuration"
+    run("cfg0.qwz_quantize", Bytes.quantize(n, 256, 8), lambda: zpp.qwz_quantize(x, 256, 8, codes=c, scales=s), note)
+    run("cfg0.qwz_dequantize", Bytes.dequantize(n, 256, 8), lambda: zpp.qwz_dequantize(c, s, n, 256, 8, out=x), note)
+    # the same kernels on 1024 such tensors in one launch
+    n = 1024 << 20
+    x = workloads.weights(n, device=dev, tensor_id=30, dtype=torch.float16, outlier_prob=0.0)
+    c, s = zpp.qwz_quantize(x, 256, 8)
+    run("cfg0x1024.qwz_quantize", Bytes.quantize(n, 256, 8), lambda: zpp.qwz_quantize(x, 256, 8, codes=c, scales=s))
+    run("cfg0x1024.qwz_dequantize", Bytes.dequantize(n, 256, 8), lambda: zpp.qwz_dequantize(c, s, n, 256, 8, out=x))
+    del x, c, s
+
+    # configs[1]: one layer, hidden 8192, bf16, P = 8 shards per matrix, int8 block 2048
+    P, B = 8, 2048
+    shapes = workloads.gpt_layer_shapes(8192)
+    n_total = sum(r * c_ for _, r, c_ in shapes)
+    w = workloads.weights(n_total, device=dev, tensor_id=10)
+    codes = torch.empty(n_total, dtype=torch.uint8, device=dev)
+    scales = torch.empty(n_total // B, dtype=torch.float32, device=dev)
+    shards, off = [], 0
+    for _, r, c_ in shapes:
+        sh = r * c_ // P
+        for rank in range(P):
+            shards.append((off + rank * sh, sh))
+        off += r * c_
+
+    def quantize_layer():
+        for lo, sh in shards:
+            zpp.qwz_quantize(w[lo:lo + sh], B, 8, codes=codes[lo:lo + sh], scales=scales[lo // B:(lo + sh) // B])
+
+    run("cfg1.qwz_quantize_32_shards", Bytes.quantize(n_total, B, 8), quantize_layer,
+        "32 launches (8 rank shards x 4 matrices) written at their offsets of the gather buffer")
+    run("cfg1.qwz_dequantize_layer", Bytes.dequantize(n_total, B, 8),
+        lambda: zpp.qwz_dequantize(codes, scales, n_total, B, 8, out=w))
+    del w, codes, scales
+
+    # configs[2]: 8 ranks x 2^28 fp16 heavy-tailed gradients, X = 8, Y = 64, int4 block 512
+    X, Y, B = 8, 64, 512
+    n = 1 << 28
+    m = n // X
+    grads = [workloads.gradients(n, device=dev, tensor_id=40 + r) for r in range(X)]
+    first = [zpp.qgz_reorder(g, X, Y, 1, B, 4) for g in grads]
+    it = [0]
+
+    def reorder_one():
+        r = it[0] % X
+        it[0] += 1
+        zpp.qgz_reorder(grads[r], X, Y, 1, B, 4, codes=first[r][0], scales=first[r][1])
+
+    run("cfg2.qgz_reorder_per_rank", Bytes.quantize(n, B, 4), reorder_one)
+    del grads
+    co = torch.empty(m // 2, dtype=torch.uint8, device=dev)
+    so = torch.empty(m // B, dtype=torch.float32, device=dev)
+    cb, sb = m // 2, m // B
+
+    def intra_one():
+        j = it[0] % X
+        it[0] += 1
+        zpp.qgz_intra_reduce([f[0][j * cb:(j + 1) * cb] for f in first], [f[1][j * sb:(j + 1) * sb] for f in first],
+                             m, B, 4, codes_out=co, scales_out=so)
+
+    run("cfg2.qgz_intra_reduce_per_rank", Bytes.intra(m, B, 4, X), intra_one)
+    del first, co, so
+
+    # configs[3]: 48 node chunks of 46,875,136 elements (46,875,000 padded to the block), int4 block 512
+    Y, L = 48, 46875136
+    enc = []
+    for i in range(Y):
+        g = workloads.gradients(L, device=dev, tensor_id=60 + i, tail_std=0.0)
+        enc.append(zpp.qwz_quantize(g, B, 4))
+        del g
+    out = torch.empty(L, dtype=torch.float32, device=dev)
+    run("cfg3.qgz_inter_reduce", Bytes.inter(L, B, 4, Y),
+        lambda: zpp.qgz_inter_reduce([c_ for c_, _ in enc], [s_ for _, s_ in enc], L, B, 4, 384.0, out=out))
+    return res
 
 
 def cpu_baseline(args, n_L, X, Y, W, WB, WBITS, GB_, GBITS):
