@@ -40,10 +40,83 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define ZPP_RED_MIN_WAVES 8192
 #endif
 
+// optional cap on resident waves per SIMD for the streaming kernels (0 = none)
+#ifndef ZPP_QUANT_WAVES
+#define ZPP_QUANT_WAVES 0
+#endif
+#ifndef ZPP_DEQ_WAVES
+#define ZPP_DEQ_WAVES 0
+#endif
+#if ZPP_QUANT_WAVES > 0
+#define ZPP_QUANT_OCC __attribute__((amdgpu_waves_per_eu(1, ZPP_QUANT_WAVES)))
+#else
+#define ZPP_QUANT_OCC
+#endif
+#if ZPP_DEQ_WAVES > 0
+#define ZPP_DEQ_OCC __attribute__((amdgpu_waves_per_eu(1, ZPP_DEQ_WAVES)))
+#else
+#define ZPP_DEQ_OCC
+#endif
+
 constexpr int kWave = 64;
 constexpr int kWavesPerWG = 4;
 constexpr int kThreads = kWave * kWavesPerWG;
 constexpr float kTiny = 0x1p-100f;  // blocks with a smaller maximum are coded as all zero
+
+// streaming accesses: every byte is touched once, so loads and stores carry the
+// non-temporal hint (ZPP_NT_LOAD / ZPP_NT_STORE = 0 switch it off for experiments)
+#ifndef ZPP_NT_LOAD
+#define ZPP_NT_LOAD 1
+#endif
+#ifndef ZPP_NT_STORE
+#define ZPP_NT_STORE 1
+#endif
+template <class T>
+__device__ __forceinline__ T ld_stream(const T* p)
+{
+#if ZPP_NT_LOAD
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <class T>
+__device__ __forceinline__ void st_stream(T v, T* p)
+{
+#if ZPP_NT_STORE
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by their index.  For large grids
+// the quantize and dequantize kernels remap the index so that each XCD works through
+// runs of 2^ZPP_XCD_SHIFT consecutive tiles (measured 2-4 % faster than interleaving
+// single tiles over the XCDs).  The grid is then padded to a multiple of 8 runs and
+// surplus groups exit at once; small grids keep the plain order (shift < 0).
+#ifndef ZPP_XCD_SHIFT
+#define ZPP_XCD_SHIFT 6
+#endif
+constexpr uint64_t kXcdMinGrid = 16ull * 8ull << (ZPP_XCD_SHIFT > 0 ? ZPP_XCD_SHIFT : 0);
+
+__device__ __forceinline__ uint64_t logical_block(int xcd_shift)
+{
+    const uint32_t b = blockIdx.x;
+    if (xcd_shift < 0) return b;
+    const uint32_t x = b & 7u, r = b >> 3;
+    return ((((uint64_t)(r >> xcd_shift) << 3) + x) << xcd_shift) + (r & ((1u << xcd_shift) - 1u));
+}
+
+// grid size and remap shift for `groups` workgroups of real work
+inline uint64_t plan_grid(uint64_t groups, int& xcd_shift)
+{
+    xcd_shift = -1;
+    if (ZPP_XCD_SHIFT < 0 || groups < kXcdMinGrid) return groups;
+    xcd_shift = ZPP_XCD_SHIFT;
+    const uint64_t q = 8ull << ZPP_XCD_SHIFT;
+    return (groups + q - 1) / q * q;
+}
 
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
@@ -119,12 +192,12 @@ __device__ __forceinline__ void load8(const void* __restrict__ base, uint64_t e,
 {
     if (DT == ZPP_F32) {
         const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + e);
-        f32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
+        f32x4 a = ld_stream(p), b = ld_stream(p + 1);
         f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
         f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
     } else {
         const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + e);
-        u32x4 w = __builtin_nontemporal_load(p);
+        u32x4 w = ld_stream(p);
         widen2<DT>(w.x, f[0], f[1]);
         widen2<DT>(w.y, f[2], f[3]);
         widen2<DT>(w.z, f[4], f[5]);
@@ -175,11 +248,11 @@ __device__ __forceinline__ void store_codes8(uint8_t* __restrict__ codes, uint64
         u32x2 o;
         o.x = (c[0] & 0xffu) | ((c[1] & 0xffu) << 8) | ((c[2] & 0xffu) << 16) | (c[3] << 24);
         o.y = (c[4] & 0xffu) | ((c[5] & 0xffu) << 8) | ((c[6] & 0xffu) << 16) | (c[7] << 24);
-        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(codes + e));
+        st_stream(o, reinterpret_cast<u32x2*>(codes + e));
     } else {
         uint32_t o = (c[0] & 0xfu) | ((c[1] & 0xfu) << 4) | ((c[2] & 0xfu) << 8) | ((c[3] & 0xfu) << 12) |
                      ((c[4] & 0xfu) << 16) | ((c[5] & 0xfu) << 20) | ((c[6] & 0xfu) << 24) | (c[7] << 28);
-        __builtin_nontemporal_store(o, reinterpret_cast<uint32_t*>(codes + (e >> 1)));
+        st_stream(o, reinterpret_cast<uint32_t*>(codes + (e >> 1)));
     }
 }
 
@@ -211,15 +284,15 @@ __device__ __host__ __forceinline__ uint64_t source_slice(uint64_t p, uint32_t X
 // the wave); smaller blocks sit inside one load, B/8 lanes each.
 
 template <int DT, int BITS, int LOG2B, int V>
-__global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
+__global__ __launch_bounds__(kThreads) ZPP_QUANT_OCC void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                                        float* __restrict__ scales, uint64_t L,
                                                        uint64_t tiles_per_slice, uint64_t total_tiles,
-                                                       uint32_t X, uint32_t Y)
+                                                       uint32_t X, uint32_t Y, int xcd_shift)
 {
     constexpr int B = 1 << LOG2B;
     constexpr int TILE = 512 * V;
     const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wid >= total_tiles) return;
     const uint64_t p = wid / tiles_per_slice, t = wid % tiles_per_slice;
     const uint64_t src = (X == 1 || Y == 1) ? p : source_slice(p, X, Y);
@@ -334,14 +407,14 @@ __device__ __forceinline__ float byte_f32(uint32_t w, int i)
 // full-width contiguous stores.
 
 template <int ODT, int BITS, int V>
-__global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restrict__ codes,
+__global__ __launch_bounds__(kThreads) ZPP_DEQ_OCC void k_dequantize(const uint8_t* __restrict__ codes,
                                                          const float* __restrict__ scales,
                                                          void* __restrict__ y, uint64_t n, uint32_t B,
-                                                         int log2b /* -1: not a power of two */)
+                                                         int log2b /* -1: not a power of two */, int xcd_shift)
 {
     constexpr int TILE = 512 * V;
     const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t base = wid * TILE;
     if (base >= n) return;
     const uint64_t rem = n - base;
@@ -358,11 +431,11 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restri
         if (ok[k]) {
             const uint64_t e = base + off;
             if (BITS == 8) {
-                u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(codes + e));
+                u32x2 v = ld_stream(reinterpret_cast<const u32x2*>(codes + e));
                 w[k][0] = v.x;
                 w[k][1] = v.y;
             } else {
-                w[k][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(codes + (e >> 1)));
+                w[k][0] = ld_stream(reinterpret_cast<const uint32_t*>(codes + (e >> 1)));
             }
             const uint64_t blk = log2b >= 0 ? (e >> log2b) : (e / B);
             s[k] = scales[blk];
@@ -386,15 +459,15 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restri
         if (ODT == ZPP_F32) {
             f32x4* o = reinterpret_cast<f32x4*>(static_cast<float*>(y) + e);
             f32x4 a = {d[0], d[1], d[2], d[3]}, b = {d[4], d[5], d[6], d[7]};
-            __builtin_nontemporal_store(a, o);
-            __builtin_nontemporal_store(b, o + 1);
+            st_stream(a, o);
+            st_stream(b, o + 1);
         } else {
             u32x4 o;
             o.x = narrow2<ODT>(d[0], d[1]);
             o.y = narrow2<ODT>(d[2], d[3]);
             o.z = narrow2<ODT>(d[4], d[5]);
             o.w = narrow2<ODT>(d[6], d[7]);
-            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(y) + e));
+            st_stream(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(y) + e));
         }
     }
 }
@@ -418,13 +491,13 @@ template <int NW>
 __device__ __forceinline__ void load_words(const uint8_t* __restrict__ p, uint32_t (&w)[NW])
 {
     if constexpr (NW == 4) {
-        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(p));
         w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
     } else if constexpr (NW == 2) {
-        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+        const u32x2 v = ld_stream(reinterpret_cast<const u32x2*>(p));
         w[0] = v.x; w[1] = v.y;
     } else {
-        w[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+        w[0] = ld_stream(reinterpret_cast<const uint32_t*>(p));
     }
 }
 
@@ -585,7 +658,7 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
         od[j] = v;
     }
     o.x = od[0]; o.y = od[1]; o.z = od[2]; o.w = od[3];
-    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(codes_out + e * BITS / 8));
+    st_stream(o, reinterpret_cast<u32x4*>(codes_out + e * BITS / 8));
 }
 
 // qgz_intra_reduce for any other block size: one wave per block, the sums wait in
@@ -687,7 +760,7 @@ __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, in
         const uint32_t c = (uint32_t)j * kWave + lane;  // chunk of the tile this lane stores now
         const uint32_t src_lane = c / CH, src_i = c % CH;
         const f32x4 v = mine[src_lane * CH + (src_i ^ (src_lane & (CH - 1)))];
-        if (c < chunks) __builtin_nontemporal_store(v, o + c);
+        if (c < chunks) st_stream(v, o + c);
     }
 }
 
@@ -700,10 +773,10 @@ __global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src
     u32x4 v[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-        if (i0 + (uint64_t)k * kThreads < nvec) v[k] = __builtin_nontemporal_load(src + i0 + (uint64_t)k * kThreads);
+        if (i0 + (uint64_t)k * kThreads < nvec) v[k] = ld_stream(src + i0 + (uint64_t)k * kThreads);
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-        if (i0 + (uint64_t)k * kThreads < nvec) __builtin_nontemporal_store(v[k], dst + i0 + (uint64_t)k * kThreads);
+        if (i0 + (uint64_t)k * kThreads < nvec) st_stream(v[k], dst + i0 + (uint64_t)k * kThreads);
 }
 
 // ---------------------------------------------------------------------------
@@ -730,9 +803,10 @@ int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t
     constexpr int V = (1 << LOG2B) / 512 > ZPP_QUANT_V ? (1 << LOG2B) / 512 : ZPP_QUANT_V;
     const uint64_t tps = (L + 512 * V - 1) / (512 * V);
     const uint64_t tiles = tps * slices;
-    const uint64_t grid = (tiles + kWavesPerWG - 1) / kWavesPerWG;
+    int xcd_shift;
+    const uint64_t grid = plan_grid((tiles + kWavesPerWG - 1) / kWavesPerWG, xcd_shift);
     if (grid > kMaxGrid) return ZPP_EINVAL;
-    k_quantize<DT, BITS, LOG2B, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, tps, tiles, X, Y);
+    k_quantize<DT, BITS, LOG2B, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, tps, tiles, X, Y, xcd_shift);
     return launch_status();
 }
 
@@ -752,7 +826,7 @@ int launch_quantize(const void* x, uint8_t* codes, float* scales, uint64_t L, ui
     default: break;
     }
     const uint64_t blocks = L / B * slices;
-    const uint64_t grid = (blocks + kWavesPerWG - 1) / kWavesPerWG;
+    const uint64_t grid = ((blocks + kWavesPerWG - 1) / kWavesPerWG);
     if (grid > kMaxGrid) return ZPP_EINVAL;
     k_quantize_anyblock<DT, BITS><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, B, blocks, X, Y);
     return launch_status();
@@ -781,7 +855,7 @@ int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* cod
     constexpr int E = EPL<BITS>::value;
     const int l2 = log2_or_neg(B);
     const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
-    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    const uint64_t grid = ((waves + kWavesPerWG - 1) / kWavesPerWG);
     if (grid > kMaxGrid || m / B > kMaxGrid) return ZPP_EINVAL;
 #define ZPP_I(L2)                                                                                               \
     case L2:                                                                                                    \
@@ -888,12 +962,13 @@ int qwz_dequantize(const void* codes, const float* scales, size_t n, int block, 
     if (!y || !codes || !scales || !aligned(y, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return ZPP_EINVAL;
     constexpr int V = ZPP_DEQ_V;
     const uint64_t waves = (n + 512 * V - 1) / (512 * V);
-    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    int xcd_shift;
+    const uint64_t grid = plan_grid((waves + kWavesPerWG - 1) / kWavesPerWG, xcd_shift);
     if (grid > kMaxGrid) return ZPP_EINVAL;
     const uint8_t* c = static_cast<const uint8_t*>(codes);
     const int l2 = log2_or_neg((uint32_t)block);
     hipStream_t st = static_cast<hipStream_t>(stream);
-#define ZPP_D(ODT, BITS) k_dequantize<ODT, BITS, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2)
+#define ZPP_D(ODT, BITS) k_dequantize<ODT, BITS, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift)
     if (bits == 8) {
         if (out_dtype == ZPP_F16) ZPP_D(ZPP_F16, 8);
         else if (out_dtype == ZPP_BF16) ZPP_D(ZPP_BF16, 8);
@@ -938,7 +1013,7 @@ int qgz_inter_reduce(const void* const* codes_in, const float* const* scales_in,
     while (nw > 1 && (m + (uint64_t)kWave * nw * per_dword - 1) / ((uint64_t)kWave * nw * per_dword) < ZPP_RED_MIN_WAVES) nw >>= 1;
     const uint64_t per_wave = (uint64_t)kWave * nw * per_dword;
     const uint64_t waves = (m + per_wave - 1) / per_wave;
-    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    const uint64_t grid = ((waves + kWavesPerWG - 1) / kWavesPerWG);
     if (grid > kMaxGrid) return ZPP_EINVAL;
 #define ZPP_R(BITS, NW) k_inter_reduce<BITS, NW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, recip, out)
     if (bits == 4) {

@@ -101,6 +101,27 @@ def test_qwz_round_trip_bit_exact(dtype, bits, block, blocks):
         assert_guards_intact(yfull, n, TORCH_DT[odt])
 
 
+@pytest.mark.parametrize("dtype,bits,block,blocks", [(oracle.BF16, 8, 2048, 16411), (oracle.F16, 8, 256, 270001),
+                                                      (oracle.F16, 4, 512, 131075)])
+def test_qwz_round_trip_large_grid(dtype, bits, block, blocks):
+    """Large enough that the kernels remap workgroups over the XCDs (grids of more
+    than 8192 groups), with a ragged last tile; still element by element."""
+    n = block * blocks
+    x = make_input(n, dtype, "weights", seed=blocks)
+    want_codes, want_scales = oracle.qwz_quantize(host_bits(x), dtype, block, bits)
+    cfull, codes = guarded(n * bits // 8, torch.uint8)
+    sfull, scales = guarded(n // block, torch.float32)
+    zpp.qwz_quantize(x.to(DEV), block, bits, codes=codes, scales=scales)
+    yfull, y = guarded(n, TORCH_DT[dtype])
+    zpp.qwz_dequantize(codes, scales, n, block, bits, out=y)
+    torch.cuda.synchronize()
+    assert eq_bytes(scales, want_scales) and eq_bytes(codes, want_codes)
+    assert eq_bytes(y, oracle.qwz_dequantize(want_codes, want_scales, n, block, bits, dtype))
+    assert_guards_intact(cfull, n * bits // 8, torch.uint8)
+    assert_guards_intact(sfull, n // block, torch.float32)
+    assert_guards_intact(yfull, n, TORCH_DT[dtype])
+
+
 def test_qwz_shards_written_at_offsets_equal_whole_tensor():
     """The simulated all-gather: P ranks quantize their shard straight into their
     slot of the gather buffer; the result is the whole tensor's quantization."""
@@ -193,6 +214,7 @@ REORDER_CASES = [
     (8, 2, 1, 2048, 4, 3),
     (1, 7, 1, 256, 4, 5),
     (16, 1, 2, 128, 8, 3),
+    (8, 6, 1, 512, 4, 2731),       # 8193+ workgroups: the XCD remap is active, tiles end ragged in every slice
 ]
 
 
