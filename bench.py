@@ -124,6 +124,10 @@ def main():
         node_sets.append(([c[i * L // 2:(i + 1) * L // 2] for i in range(Y - 1)],
                           [sc[i * L // GB_:(i + 1) * L // GB_] for i in range(Y - 1)]))
     gout = torch.empty(L, dtype=torch.float32, device=dev)
+    # pointer tables of the two simulated all-to-alls: this GPU's own piece first, then the others'
+    intra_tables = [zpp.PeerTable([gcodes[:m // 2]] + [p[0] for p in peers], [gscales[:m // GB_]] + [p[1] for p in peers])
+                    for peers in peer_sets]
+    inter_tables = [zpp.PeerTable([icodes[:L // 2]] + nc, [iscales[:L // GB_]] + ns) for nc, ns in node_sets]
     setup_s = time.time() - t0
 
     bytes_per = {
@@ -155,14 +159,9 @@ def main():
         for l in reversed(range(layers)):                         # backward
             timed("qwz_dequantize", lambda: zpp.qwz_dequantize(wcodes, wscales, n_L, WB, WBITS, out=wout), record)
             timed("qgz_reorder", lambda: zpp.qgz_reorder(grad, X, Y, 1, GB_, GBITS, codes=gcodes, scales=gscales), record)
-            peers = peer_sets[l % 2]
-            cin = [gcodes[:m // 2]] + [p[0] for p in peers]
-            sin = [gscales[:m // GB_]] + [p[1] for p in peers]
-            timed("qgz_intra_reduce", lambda: zpp.qgz_intra_reduce(cin, sin, m, GB_, GBITS, codes_out=icodes, scales_out=iscales), record)
-            nc, ns = node_sets[l % 8]
-            cin2 = [icodes[:L // 2]] + nc
-            sin2 = [iscales[:L // GB_]] + ns
-            timed("qgz_inter_reduce", lambda: zpp.qgz_inter_reduce(cin2, sin2, L, GB_, GBITS, float(W), out=gout), record)
+            it, nt = intra_tables[l % 2], inter_tables[l % 8]
+            timed("qgz_intra_reduce", lambda: zpp.qgz_intra_reduce(it, None, m, GB_, GBITS, codes_out=icodes, scales_out=iscales), record)
+            timed("qgz_inter_reduce", lambda: zpp.qgz_inter_reduce(nt, None, L, GB_, GBITS, float(W), out=gout), record)
             timed("qwz_quantize", lambda: zpp.qwz_quantize(own, WB, WBITS, codes=own_codes, scales=own_scales), record)
 
     for _ in range(args.warmup):
@@ -214,7 +213,7 @@ def main():
                 "algorithmic_bytes_per_launch": bytes_per[dom], "avg_launch_ms": kernels[dom]["avg_ms"],
                 "copy_ceiling_GBps": round(copy_gbs, 1)}
 
-    del w, wout, grad, gcodes, gscales, peer_sets, node_sets, wcodes, src, dst
+    del w, wout, grad, gcodes, gscales, peer_sets, node_sets, wcodes, src, dst, intra_tables, inter_tables
     torch.cuda.empty_cache()
     per_config = None if args.no_configs else per_config_kernels(torch, zpp, workloads, dev)
 
@@ -239,22 +238,30 @@ def main():
 
 
 def per_config_kernels(torch, zpp, workloads, dev):
-    """Each kernel alone at the shapes of configs[0..3]: median of 20 launches after 3
-    warm-ups, HIP events on the launch stream.  GB/s of algorithmic bytes."""
+    """Each kernel alone at the shapes of configs[0..3], HIP events on the launch stream,
+    GB/s of algorithmic bytes (see run() for the protocol)."""
     res = {}
 
-    def run(name, nbytes, fn, note=None):
+    blk_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    blk_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+
+    def run(name, nbytes, fn, note=None, batch=10, rounds=7):
+        """Median over `rounds` of (time of `batch` back-to-back launches) / batch.  A 1 GiB copy
+        is queued in front of each batch so that the host is ahead of the GPU when the first
+        event is reached: short kernels are then timed at the GPU's pace, not the host's."""
         for _ in range(3):
             fn()
         ev = []
-        for _ in range(20):
+        for _ in range(rounds):
+            zpp.stream_copy(blk_dst, blk_src)
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-            fn()
+            for _ in range(batch):
+                fn()
             b.record()
             ev.append((a, b))
         torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        ms = sorted(a.elapsed_time(b) / batch for a, b in ev)
         med = ms[len(ms) // 2]
         gbs = nbytes / (med * 1e-3) / 1e9
         res[name] = {"bytes": int(nbytes), "median_us": round(med * 1e3, 2), "min_us": round(ms[0] * 1e3, 2),
@@ -296,9 +303,9 @@ def per_config_kernels(torch, zpp, workloads, dev):
             zpp.qwz_quantize(w[lo:lo + sh], B, 8, codes=codes[lo:lo + sh], scales=scales[lo // B:(lo + sh) // B])
 
     run("cfg1.qwz_quantize_32_shards", Bytes.quantize(n_total, B, 8), quantize_layer,
-        "32 launches (8 rank shards x 4 matrices) written at their offsets of the gather buffer")
+        "32 launches (8 rank shards x 4 matrices) written at their offsets of the gather buffer", batch=2)
     run("cfg1.qwz_dequantize_layer", Bytes.dequantize(n_total, B, 8),
-        lambda: zpp.qwz_dequantize(codes, scales, n_total, B, 8, out=w))
+        lambda: zpp.qwz_dequantize(codes, scales, n_total, B, 8, out=w), batch=4)
     del w, codes, scales
 
     # configs[2]: 8 ranks x 2^28 fp16 heavy-tailed gradients, X = 8, Y = 64, int4 block 512
@@ -320,14 +327,16 @@ def per_config_kernels(torch, zpp, workloads, dev):
     so = torch.empty(m // B, dtype=torch.float32, device=dev)
     cb, sb = m // 2, m // B
 
+    tables = [zpp.PeerTable([f[0][j * cb:(j + 1) * cb] for f in first], [f[1][j * sb:(j + 1) * sb] for f in first])
+              for j in range(X)]
+
     def intra_one():
         j = it[0] % X
         it[0] += 1
-        zpp.qgz_intra_reduce([f[0][j * cb:(j + 1) * cb] for f in first], [f[1][j * sb:(j + 1) * sb] for f in first],
-                             m, B, 4, codes_out=co, scales_out=so)
+        zpp.qgz_intra_reduce(tables[j], None, m, B, 4, codes_out=co, scales_out=so)
 
     run("cfg2.qgz_intra_reduce_per_rank", Bytes.intra(m, B, 4, X), intra_one)
-    del first, co, so
+    del first, co, so, tables
 
     # configs[3]: 48 node chunks of 46,875,136 elements (46,875,000 padded to the block), int4 block 512
     Y, L = 48, 46875136
@@ -337,8 +346,9 @@ def per_config_kernels(torch, zpp, workloads, dev):
         enc.append(zpp.qwz_quantize(g, B, 4))
         del g
     out = torch.empty(L, dtype=torch.float32, device=dev)
+    table = zpp.PeerTable([c_ for c_, _ in enc], [s_ for _, s_ in enc])
     run("cfg3.qgz_inter_reduce", Bytes.inter(L, B, 4, Y),
-        lambda: zpp.qgz_inter_reduce([c_ for c_, _ in enc], [s_ for _, s_ in enc], L, B, 4, 384.0, out=out))
+        lambda: zpp.qgz_inter_reduce(table, None, L, B, 4, 384.0, out=out), batch=4)
     return res
 
 

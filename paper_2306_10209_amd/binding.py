@@ -132,31 +132,49 @@ def qgz_reorder(grad, X, Y, S, block, bits=4, codes=None, scales=None, stream=No
 def _table(tensors, name):
     if len(tensors) == 0:
         raise ZppError(f"{name}: empty pointer table")
-    arr = (ctypes.c_void_p * len(tensors))(*[_dev(t, name) for t in tensors])
-    return arr
+    return (ctypes.c_void_p * len(tensors))(*[_dev(t, name) for t in tensors])
+
+
+class PeerTable:
+    """Host arrays of device pointers for the reduce stages, built once and reusable
+    across launches (the library copies them into each launch).  Keeps the tensors
+    alive."""
+
+    def __init__(self, codes_in, scales_in):
+        if len(codes_in) != len(scales_in):
+            raise ZppError("codes_in and scales_in differ in length")
+        self.count = len(codes_in)
+        self.codes = _table(codes_in, "codes_in")
+        self.scales = _table(scales_in, "scales_in")
+        self.device = codes_in[0].device
+        self._keep = (list(codes_in), list(scales_in))
+
+
+def _peers(codes_in, scales_in):
+    if isinstance(codes_in, PeerTable):
+        return codes_in
+    return PeerTable(codes_in, scales_in)
 
 
 def qgz_intra_reduce(codes_in, scales_in, m, block, bits=4, codes_out=None, scales_out=None, stream=None):
-    _table(codes_in, "codes_in")
-    dev = codes_in[0].device
+    """codes_in / scales_in: lists of device tensors, or a PeerTable as codes_in (scales_in ignored)."""
+    t = _peers(codes_in, scales_in)
     if codes_out is None:
-        codes_out = torch.empty(m * bits // 8, dtype=torch.uint8, device=dev)
+        codes_out = torch.empty(m * bits // 8, dtype=torch.uint8, device=t.device)
     if scales_out is None:
-        scales_out = torch.empty(m // block if block > 0 else 0, dtype=torch.float32, device=dev)
-    _check(lib().qgz_intra_reduce(_table(codes_in, "codes_in"), _table(scales_in, "scales_in"), len(codes_in),
-                                  m, block, bits, _dev(codes_out, "codes_out"), _dev(scales_out, "scales_out"),
-                                  _stream(stream)), "qgz_intra_reduce")
+        scales_out = torch.empty(m // block if block > 0 else 0, dtype=torch.float32, device=t.device)
+    _check(lib().qgz_intra_reduce(t.codes, t.scales, t.count, m, block, bits, _dev(codes_out, "codes_out"),
+                                  _dev(scales_out, "scales_out"), _stream(stream)), "qgz_intra_reduce")
     return codes_out, scales_out
 
 
 def qgz_inter_reduce(codes_in, scales_in, m, block, bits=4, divisor=1.0, out=None, stream=None):
-    _table(codes_in, "codes_in")
-    dev = codes_in[0].device
+    """codes_in / scales_in: lists of device tensors, or a PeerTable as codes_in (scales_in ignored)."""
+    t = _peers(codes_in, scales_in)
     if out is None:
-        out = torch.empty(m, dtype=torch.float32, device=dev)
-    _check(lib().qgz_inter_reduce(_table(codes_in, "codes_in"), _table(scales_in, "scales_in"), len(codes_in),
-                                  m, block, bits, float(divisor), _dev(out, "out"), _stream(stream)),
-           "qgz_inter_reduce")
+        out = torch.empty(m, dtype=torch.float32, device=t.device)
+    _check(lib().qgz_inter_reduce(t.codes, t.scales, t.count, m, block, bits, float(divisor), _dev(out, "out"),
+                                  _stream(stream)), "qgz_inter_reduce")
     return out
 
 

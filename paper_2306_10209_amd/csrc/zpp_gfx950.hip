@@ -35,9 +35,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef ZPP_RED_PREFETCH
 #define ZPP_RED_PREFETCH true
 #endif
-// reduce stages: fewest waves for which a lane takes the widest code vector
-#ifndef ZPP_RED_MIN_WAVES
-#define ZPP_RED_MIN_WAVES 8192
+// qgz_inter_reduce: code dwords a lane takes per peer (1, 2 or 4)
+#ifndef ZPP_INTER_NW
+#define ZPP_INTER_NW 1
 #endif
 
 // optional cap on resident waves per SIMD for the streaming kernels (0 = none)
@@ -227,32 +227,45 @@ __device__ __forceinline__ void block_scale(float a, float& scale, float& inv)
     }
 }
 
-// Code of one value: roundeven(v * inv).  Adding 1.5*2^23 rounds the product to
-// an integer with the adder's own round-to-nearest-even and leaves it, in two's
-// complement, in the low mantissa bits.  |v*inv| <= qmax + 2^-17 for finite
-// input, so no clamp is needed.
-__device__ __forceinline__ uint32_t code_bits(float v, float inv)
+// Code of one value: roundeven(v * inv).  Adding 1.5*2^23 + bias rounds the product
+// to an integer with the adder's own round-to-nearest-even and leaves code + bias
+// in the low mantissa bits (bits = 0x4B400000 + bias + code).  |v*inv| <= qmax + 2^-17
+// for finite input, so no clamp is needed.  With bias = qmax + 1 the low field is the
+// non-negative u = code + bias, which lets several codes be packed with shift-adds:
+// the upper bits of every term add up to a constant (mod 2^32) that is taken off at
+// the end, and flipping each field's top bit turns u into the two's-complement code.
+template <int BITS>
+__device__ __forceinline__ uint32_t biased_code_bits(float v, float inv)
 {
-    float t = v * inv;
-    return as_u32(t + 12582912.0f);
+    const float t = v * inv;
+    return as_u32(t + (12582912.0f + (float)(1 << (BITS - 1))));
+}
+
+// FIELDS codes of BITS bits each -> one dword (FIELDS * BITS == 32)
+template <int BITS>
+__device__ __forceinline__ uint32_t pack_dword(const float* __restrict__ f, float inv)
+{
+    constexpr int FIELDS = 32 / BITS;
+    uint32_t acc = biased_code_bits<BITS>(f[FIELDS - 1], inv);
+#pragma unroll
+    for (int i = FIELDS - 2; i >= 0; --i) acc = (acc << BITS) + biased_code_bits<BITS>(f[i], inv);
+    constexpr uint32_t ones = BITS == 4 ? 0x11111111u : 0x01010101u;  // sum of 2^(BITS*i)
+    constexpr uint32_t upper = 0x4B400000u * ones;                    // what the exponent bits added up to
+    constexpr uint32_t flip = ones << (BITS - 1);
+    return (acc - upper) ^ flip;
 }
 
 // eight codes -> packed storage
 template <int BITS>
 __device__ __forceinline__ void store_codes8(uint8_t* __restrict__ codes, uint64_t e, const float (&f)[8], float inv)
 {
-    uint32_t c[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) c[i] = code_bits(f[i], inv);
     if (BITS == 8) {
         u32x2 o;
-        o.x = (c[0] & 0xffu) | ((c[1] & 0xffu) << 8) | ((c[2] & 0xffu) << 16) | (c[3] << 24);
-        o.y = (c[4] & 0xffu) | ((c[5] & 0xffu) << 8) | ((c[6] & 0xffu) << 16) | (c[7] << 24);
+        o.x = pack_dword<8>(f, inv);
+        o.y = pack_dword<8>(f + 4, inv);
         st_stream(o, reinterpret_cast<u32x2*>(codes + e));
     } else {
-        uint32_t o = (c[0] & 0xfu) | ((c[1] & 0xfu) << 4) | ((c[2] & 0xfu) << 8) | ((c[3] & 0xfu) << 12) |
-                     ((c[4] & 0xfu) << 16) | ((c[5] & 0xfu) << 20) | ((c[6] & 0xfu) << 24) | (c[7] << 28);
-        st_stream(o, reinterpret_cast<uint32_t*>(codes + (e >> 1)));
+        st_stream(pack_dword<4>(f, inv), reinterpret_cast<uint32_t*>(codes + (e >> 1)));
     }
 }
 
@@ -516,12 +529,12 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w, float s_lo, float s_hi,
                                              float bias)
 {
-    const uint32_t u = w ^ 0x88888888u;
-    const uint32_t v = u >> 8;
-    const f16x2 a = __builtin_bit_cast(f16x2, u & 0x000F000Fu);  // elements 0, 4
-    const f16x2 b = __builtin_bit_cast(f16x2, u & 0x00F000F0u);  // elements 1, 5
-    const f16x2 c = __builtin_bit_cast(f16x2, v & 0x000F000Fu);  // elements 2, 6
-    const f16x2 d = __builtin_bit_cast(f16x2, v & 0x00F000F0u);  // elements 3, 7
+    // (x ^ 0x88888888) & mask in one three-input bit operation each
+    const uint32_t v = w >> 8;
+    const f16x2 a = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(w, 0x88888888u, 0x000F000Fu, 0x28));  // elements 0, 4
+    const f16x2 b = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(w, 0x88888888u, 0x00F000F0u, 0x28));  // elements 1, 5
+    const f16x2 c = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(v, 0x88888888u, 0x000F000Fu, 0x28));  // elements 2, 6
+    const f16x2 d = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(v, 0x88888888u, 0x00F000F0u, 0x28));  // elements 3, 7
     acc[0] = acc[0] + __builtin_fmaf((float)a.x, s_lo, bias);
     acc[1] = acc[1] + __builtin_fmaf((float)b.x, s_hi, bias);
     acc[2] = acc[2] + __builtin_fmaf((float)c.x, s_lo, bias);
@@ -644,20 +657,11 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
     if (!ok) return;
     if ((lane & (G - 1)) == 0) scales_out[e >> LOG2B] = scale;
     u32x4 o;
-    uint32_t od[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        uint32_t v = 0;
-        if (BITS == 4) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v |= (code_bits(acc[j * 8 + i], inv) & 0xfu) << (4 * i);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) v |= (code_bits(acc[j * 4 + i], inv) & 0xffu) << (8 * i);
-        }
-        od[j] = v;
-    }
-    o.x = od[0]; o.y = od[1]; o.z = od[2]; o.w = od[3];
+    constexpr int FIELDS = 32 / BITS;
+    o.x = pack_dword<BITS>(acc, inv);
+    o.y = pack_dword<BITS>(acc + FIELDS, inv);
+    o.z = pack_dword<BITS>(acc + 2 * FIELDS, inv);
+    o.w = pack_dword<BITS>(acc + 3 * FIELDS, inv);
     st_stream(o, reinterpret_cast<u32x4*>(codes_out + e * BITS / 8));
 }
 
@@ -1007,24 +1011,16 @@ int qgz_inter_reduce(const void* const* codes_in, const float* const* scales_in,
     const int l2 = log2_or_neg((uint32_t)block);
     int dexp = 0;
     const float recip = (frexpf(divisor, &dexp) == 0.5f && dexp >= -125) ? 1.0f / divisor : 0.0f;
-    // widest code vector per lane that still leaves enough waves to fill the chip
-    const int per_dword = 32 / bits;
-    int nw = 4;
-    while (nw > 1 && (m + (uint64_t)kWave * nw * per_dword - 1) / ((uint64_t)kWave * nw * per_dword) < ZPP_RED_MIN_WAVES) nw >>= 1;
-    const uint64_t per_wave = (uint64_t)kWave * nw * per_dword;
+    // one code dword per lane and peer measured fastest at every size (most waves in
+    // flight; the kernel is bound by latency and issue, not by vector width)
+    constexpr int nw = ZPP_INTER_NW;
+    const uint64_t per_wave = (uint64_t)kWave * nw * (32 / bits);
     const uint64_t waves = (m + per_wave - 1) / per_wave;
-    const uint64_t grid = ((waves + kWavesPerWG - 1) / kWavesPerWG);
+    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
     if (grid > kMaxGrid) return ZPP_EINVAL;
-#define ZPP_R(BITS, NW) k_inter_reduce<BITS, NW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, recip, out)
-    if (bits == 4) {
-        if (nw == 4) ZPP_R(4, 4);
-        else if (nw == 2) ZPP_R(4, 2);
-        else ZPP_R(4, 1);
-    } else {
-        if (nw == 4) ZPP_R(8, 4);
-        else if (nw == 2) ZPP_R(8, 2);
-        else ZPP_R(8, 1);
-    }
+#define ZPP_R(BITS) k_inter_reduce<BITS, ZPP_INTER_NW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, recip, out)
+    if (bits == 4) ZPP_R(4);
+    else ZPP_R(8);
 #undef ZPP_R
     return launch_status();
 }
