@@ -201,13 +201,14 @@ def main():
     copy_gbs = 2 * (1 << 31) / (copy_ms * 1e-3) / 1e9
 
     dom = "qwz_dequantize"
+    # HBM bytes per launch measured with rocprofv3 --pmc (committed summary, see profiles/)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "bench_step_hbm_traffic.txt")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(dom, {}).get("bytes_per_launch")
-        except Exception:
-            traffic = None
+        for line in open(tpath):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "TRAFFIC" and parts[1] == dom:
+                traffic = int(parts[2].split("=")[1])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": bytes_per[dom], "avg_launch_ms": kernels[dom]["avg_ms"],
