@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=40)
     ap.add_argument("--hidden", type=int, default=12288)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-schedules", action="store_true",
+                    help="skip the timings of the Sec. 4.1 launch schedules (pipeline stages, weight prefetch)")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the per-kernel timings at the shapes of the other configurations")
     ap.add_argument("--cpu-sample-div", type=int, default=4,
@@ -214,6 +216,10 @@ def main():
                 "algorithmic_bytes_per_launch": bytes_per[dom], "avg_launch_ms": kernels[dom]["avg_ms"],
                 "copy_ceiling_GBps": round(copy_gbs, 1)}
 
+    schedules = None
+    if not args.no_schedules:
+        schedules = schedule_timings(torch, zpp, dev, n_L, X, Y, W, GB_, GBITS, WB, WBITS, grad, peer_sets[0],
+                                     node_sets[0], own, wcodes, wscales, wout)
     del w, wout, grad, gcodes, gscales, peer_sets, node_sets, wcodes, src, dst, intra_tables, inter_tables
     torch.cuda.empty_cache()
     per_config = None if args.no_configs else per_config_kernels(torch, zpp, workloads, dev)
@@ -233,9 +239,52 @@ def main():
                    "step_algorithmic_bytes": step_bytes, "calls_per_step": calls_per_step},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "other_configs": per_config,
+        "schedules": schedules,
         "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))
+
+
+def schedule_timings(torch, zpp, dev, n_L, X, Y, W, GB_, GBITS, WB, WBITS, grad, peers, nodes, own, wcodes, wscales,
+                     wout):
+    """Sec. 4.1 schedules at the benchmark's layer size: (a) the gradient path of one layer cut
+    into S pipeline stages, on one stream and with the two hops on two streams; (b) eight layers
+    of the forward weight path with the next layer's shard quantization on a side stream."""
+    from paper_2306_10209_amd.schedule import QgzPipeline, QwzPrefetch
+
+    def time_ms(fn, reps=5):
+        fn()
+        ev = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in ev)
+        return round(ms[len(ms) // 2], 4)
+
+    res = {"qgz_pipeline_ms_per_layer": {}, "qwz_prefetch_ms_8_layers": {}}
+    nc, ns = nodes
+    out = torch.empty(n_L // W, dtype=torch.float32, device=dev)
+    for S in (1, 2, 4):
+        for two in (False, True):
+            pipe = QgzPipeline(n_L, X, Y, S, GB_, GBITS, device=dev, two_streams=two)
+            pipe.bind(0, 0, peers, list(zip(nc, ns)))
+            res["qgz_pipeline_ms_per_layer"][f"S={S},{'two_streams' if two else 'one_stream'}"] = \
+                time_ms(lambda: pipe.run(grad, out, float(W)))
+            del pipe
+    L = n_L // W
+    for overlap in (False, True):
+        sched = QwzPrefetch(n_L, L, 0, WB, WBITS, device=dev, overlap=overlap)
+        for slot in range(2):
+            sched.gather_codes[slot].copy_(wcodes)
+            sched.gather_scales[slot].copy_(wscales)
+        res["qwz_prefetch_ms_8_layers"]["overlapped" if overlap else "serial"] = \
+            time_ms(lambda: sched.run([own] * 8, [wout] * 8))
+        del sched
+    return res
 
 
 def per_config_kernels(torch, zpp, workloads, dev):

@@ -768,19 +768,14 @@ __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, in
     }
 }
 
-// Plain device copy, 16 bytes per lane and step: the measured bandwidth ceiling
-// the kernels above are compared with.
+// Plain device copy, one 16-byte vector per lane: the measured bandwidth ceiling the
+// kernels above are compared with (the smallest per-workgroup footprint streams
+// fastest on this memory system).
 __global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
                                                    uint64_t nvec)
 {
-    const uint64_t i0 = ((uint64_t)blockIdx.x * kThreads) * 4 + threadIdx.x;
-    u32x4 v[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-        if (i0 + (uint64_t)k * kThreads < nvec) v[k] = ld_stream(src + i0 + (uint64_t)k * kThreads);
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-        if (i0 + (uint64_t)k * kThreads < nvec) st_stream(v[k], dst + i0 + (uint64_t)k * kThreads);
+    const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < nvec) st_stream(ld_stream(src + i), dst + i);
 }
 
 // ---------------------------------------------------------------------------
@@ -1033,7 +1028,7 @@ int zpp_stream_copy(void* dst, const void* src, size_t bytes, void* stream)
     if (bytes == 0) return ZPP_OK;
     if (!dst || !src || !aligned(dst, 16) || !aligned(src, 16)) return ZPP_EINVAL;
     const uint64_t nvec = bytes / 16;
-    const uint64_t grid = (nvec + kThreads * 4 - 1) / (kThreads * 4);
+    const uint64_t grid = (nvec + kThreads - 1) / kThreads;
     if (grid > kMaxGrid) return ZPP_EINVAL;
     k_copy<<<dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
