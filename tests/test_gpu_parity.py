@@ -396,3 +396,60 @@ def test_results_do_not_depend_on_what_the_output_held_before():
                         scales=torch.full((n // block,), float("nan"), dtype=torch.float32, device=DEV))
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+# ----------------------------------------------------------------------------
+# variants by argument
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("W,block,bits", [(8, 64, 4), (48, 512, 4), (16, 128, 8)])
+def test_one_hop_all_to_all_reduction(W, block, bits):
+    """Sec. 3.3.1: quantize once, all-to-all among all W ranks, dequantize and reduce in
+    full precision.  No reordering is needed; the reduce is qgz_inter_reduce with W peers."""
+    L = block * 5
+    n = W * L
+    grads = [workloads.gradients(n, seed=55, tensor_id=r) for r in range(W)]
+    o_q = [oracle.qwz_quantize(host_bits(g), oracle.F16, block, bits) for g in grads]
+    d_q = [zpp.qwz_quantize(g.to(DEV), block, bits) for g in grads]
+    cl, sl = L * bits // 8, L // block
+    exact = np.mean(np.stack([g.double().numpy() for g in grads]), axis=0)
+    for r in (0, W // 2, W - 1):
+        want = oracle.qgz_inter_reduce([c[r * cl:(r + 1) * cl] for c, _ in o_q], [s[r * sl:(r + 1) * sl] for _, s in o_q],
+                                       L, block, bits, float(W))
+        got = zpp.qgz_inter_reduce([c[r * cl:(r + 1) * cl] for c, _ in d_q], [s[r * sl:(r + 1) * sl] for _, s in d_q],
+                                   L, block, bits, float(W))
+        torch.cuda.synchronize()
+        assert eq_bytes(got, want)
+        # and it is the mean of the ranks' slices up to the quantization step
+        step = np.mean(np.stack([np.repeat(s[r * sl:(r + 1) * sl], block) for _, s in o_q]), axis=0) / 2
+        assert np.all(np.abs(want - exact[r * L:(r + 1) * L]) <= step * (1 + 1e-3) + 1e-12)
+
+
+@pytest.mark.parametrize("dtype", [oracle.BF16, oracle.F32])
+def test_qgz_reorder_accepts_other_gradient_dtypes(dtype):
+    X, Y, block, bits = 4, 6, 256, 8
+    n = X * Y * block * 7
+    g = workloads.gradients(n, seed=56, dtype=TORCH_DT[dtype])
+    want_codes, want_scales = oracle.qgz_reorder(host_bits(g), dtype, X, Y, 1, block, bits)
+    codes, scales = zpp.qgz_reorder(g.to(DEV), X, Y, 1, block, bits)
+    torch.cuda.synchronize()
+    assert eq_bytes(codes, want_codes) and eq_bytes(scales, want_scales)
+
+
+def test_reduce_stages_with_very_large_scales():
+    """Scales of 2^100 and above take the plain decode branch of the reduce kernels."""
+    block, m, K = 512, 512 * 9, 5
+    host, dev = [], []
+    rng = np.random.default_rng(4)
+    for k in range(K):
+        x = (rng.standard_normal(m) * 2.0 ** (96 + 6 * k)).astype(np.float32)      # block maxima up to ~2^124
+        c, s = oracle.qwz_quantize(x, oracle.F32, block, 4)
+        host.append((c, s))
+        dev.append((torch.from_numpy(c).to(DEV), torch.from_numpy(s).to(DEV)))
+    assert max(float(s.max()) for _, s in host) > 2.0 ** 110
+    wc, ws = oracle.qgz_intra_reduce([c for c, _ in host], [s for _, s in host], m, block, 4)
+    gc, gs = zpp.qgz_intra_reduce([c for c, _ in dev], [s for _, s in dev], m, block, 4)
+    wo = oracle.qgz_inter_reduce([c for c, _ in host], [s for _, s in host], m, block, 4, 4.0)
+    go = zpp.qgz_inter_reduce([c for c, _ in dev], [s for _, s in dev], m, block, 4, 4.0)
+    torch.cuda.synchronize()
+    assert eq_bytes(gc, wc) and eq_bytes(gs, ws) and eq_bytes(go, wo)
