@@ -16,32 +16,37 @@ F16, BF16, F32 = 0, 1, 2
 _lib = None
 
 
+def _load(path):
+    """Load an oracle shared library and declare its signatures."""
+    L = ctypes.CDLL(path)
+    vp, fp, sz, ci = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    L.oracle_qwz_quantize.argtypes = [vp, ci, sz, ci, ci, vp, fp]
+    L.oracle_qwz_dequantize.argtypes = [vp, fp, sz, ci, ci, ci, vp]
+    L.oracle_qgz_reorder.argtypes = [vp, ci, sz, ci, ci, ci, ci, ci, vp, fp]
+    L.oracle_qgz_intra_reduce.argtypes = [vp, vp, ci, sz, ci, ci, vp, fp]
+    L.oracle_qgz_inter_reduce.argtypes = [vp, vp, ci, sz, ci, ci, ctypes.c_float, fp]
+    for f in (L.oracle_qwz_quantize, L.oracle_qwz_dequantize, L.oracle_qgz_reorder,
+              L.oracle_qgz_intra_reduce, L.oracle_qgz_inter_reduce):
+        f.restype = ci
+    L.oracle_reorder_source_slice.argtypes = [ctypes.c_longlong, ci, ci, ci]
+    L.oracle_reorder_source_slice.restype = ctypes.c_longlong
+    L.oracle_reorder_mapped_slice.argtypes = [ctypes.c_longlong, ci, ci, ci]
+    L.oracle_reorder_mapped_slice.restype = ctypes.c_longlong
+    L.oracle_widen.argtypes = [ctypes.c_uint16, ci]
+    L.oracle_widen.restype = ctypes.c_float
+    L.oracle_narrow.argtypes = [ctypes.c_float, ci]
+    L.oracle_narrow.restype = ctypes.c_uint16
+    L.oracle_set_threads.argtypes = [ci]
+    L.oracle_set_threads.restype = ci
+    return L
+
+
 def lib():
     """Load liboracle.so, compiling it first if it is missing or stale."""
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
-        L = ctypes.CDLL(path)
-        vp, fp, sz, ci = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
-        L.oracle_qwz_quantize.argtypes = [vp, ci, sz, ci, ci, vp, fp]
-        L.oracle_qwz_dequantize.argtypes = [vp, fp, sz, ci, ci, ci, vp]
-        L.oracle_qgz_reorder.argtypes = [vp, ci, sz, ci, ci, ci, ci, ci, vp, fp]
-        L.oracle_qgz_intra_reduce.argtypes = [vp, vp, ci, sz, ci, ci, vp, fp]
-        L.oracle_qgz_inter_reduce.argtypes = [vp, vp, ci, sz, ci, ci, ctypes.c_float, fp]
-        for f in (L.oracle_qwz_quantize, L.oracle_qwz_dequantize, L.oracle_qgz_reorder,
-                  L.oracle_qgz_intra_reduce, L.oracle_qgz_inter_reduce):
-            f.restype = ci
-        L.oracle_reorder_source_slice.argtypes = [ctypes.c_longlong, ci, ci, ci]
-        L.oracle_reorder_source_slice.restype = ctypes.c_longlong
-        L.oracle_reorder_mapped_slice.argtypes = [ctypes.c_longlong, ci, ci, ci]
-        L.oracle_reorder_mapped_slice.restype = ctypes.c_longlong
-        L.oracle_widen.argtypes = [ctypes.c_uint16, ci]
-        L.oracle_widen.restype = ctypes.c_float
-        L.oracle_narrow.argtypes = [ctypes.c_float, ci]
-        L.oracle_narrow.restype = ctypes.c_uint16
-        L.oracle_set_threads.argtypes = [ci]
-        L.oracle_set_threads.restype = ci
-        _lib = L
+        # ZPP_ORACLE_LIB: a test may point at a deliberately broken build to show the pins catch it
+        _lib = _load(os.environ.get("ZPP_ORACLE_LIB") or _build.build(force=False))
     return _lib
 
 
