@@ -63,8 +63,10 @@ constexpr int kWavesPerWG = 4;
 constexpr int kThreads = kWave * kWavesPerWG;
 constexpr float kTiny = 0x1p-100f;  // blocks with a smaller maximum are coded as all zero
 
-// streaming accesses: every byte is touched once, so loads and stores carry the
-// non-temporal hint (ZPP_NT_LOAD / ZPP_NT_STORE = 0 switch it off for experiments)
+// Streaming accesses: every byte is touched once, so loads and stores carry the
+// non-temporal hint (measured: +5 % on loads, +2 % on stores against plain accesses;
+// wider-scope write-through store policies gave nothing further in these kernels).
+// ZPP_NT_LOAD / ZPP_NT_STORE = 0 switch the hint off for experiments.
 #ifndef ZPP_NT_LOAD
 #define ZPP_NT_LOAD 1
 #endif
