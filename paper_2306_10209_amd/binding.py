@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "lib", "libzpp_gfx950.so")
 
 EXPORTS = ("zpp_codes_bytes", "zpp_scales_count", "zpp_strerror", "zpp_reorder_source_slice",
            "zpp_reorder_mapped_slice", "qwz_quantize", "qwz_dequantize", "qgz_reorder",
-           "qgz_intra_reduce", "qgz_inter_reduce", "zpp_stream_copy")
+           "qgz_intra_reduce", "qgz_inter_reduce", "zpp_stream_copy", "zpp_selfcheck_block_scale")
 
 _lib = None
 
@@ -46,6 +46,8 @@ def lib():
         L.qgz_intra_reduce.argtypes = [vp, vp, ci, sz, ci, ci, vp, vp, vp]
         L.qgz_inter_reduce.argtypes = [vp, vp, ci, sz, ci, ci, ctypes.c_float, vp, vp]
         L.zpp_stream_copy.argtypes = [vp, vp, sz, vp]
+        L.zpp_selfcheck_block_scale.argtypes = [ci, ci, vp, vp]
+        L.zpp_selfcheck_block_scale.restype = ci
         for name in ("qwz_quantize", "qwz_dequantize", "qgz_reorder", "qgz_intra_reduce",
                      "qgz_inter_reduce", "zpp_stream_copy"):
             getattr(L, name).restype = ci
@@ -176,6 +178,15 @@ def qgz_inter_reduce(codes_in, scales_in, m, block, bits=4, divisor=1.0, out=Non
     _check(lib().qgz_inter_reduce(t.codes, t.scales, t.count, m, block, bits, float(divisor), _dev(out, "out"),
                                   _stream(stream)), "qgz_inter_reduce")
     return out
+
+
+def selfcheck_block_scale(bits, exponent, stream=None):
+    """Diagnostic: (mismatches of absmax/qmax, mismatches of qmax/absmax) over all 2^23
+    mantissas at one binary exponent; both must be 0."""
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    _check(lib().zpp_selfcheck_block_scale(bits, exponent, _dev(counts, "counts"), _stream(stream)),
+           "zpp_selfcheck_block_scale")
+    return tuple(int(v) for v in counts.cpu())
 
 
 def stream_copy(dst, src, stream=None):

@@ -453,3 +453,12 @@ def test_reduce_stages_with_very_large_scales():
     go = zpp.qgz_inter_reduce([c for c, _ in dev], [s for _, s in dev], m, block, 4, 4.0)
     torch.cuda.synchronize()
     assert eq_bytes(gc, wc) and eq_bytes(gs, ws) and eq_bytes(go, wo)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_block_quotient_sequences_equal_division_for_every_mantissa(bits):
+    """The encoders' short fma sequences for absmax/qmax and qmax/absmax against plain
+    division: all 2^23 mantissas at the ends of the range they are used in, at 1.0,
+    at typical weight and gradient magnitudes, and at the binades next to qmax."""
+    for exponent in (-100, -99, -24, -14, -10, -6, -1, 0, 1, 2, 3, 6, 7, 15, 64, 98, 99):
+        assert zpp.selfcheck_block_scale(bits, exponent) == (0, 0), exponent
