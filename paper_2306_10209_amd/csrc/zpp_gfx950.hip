@@ -330,6 +330,46 @@ __device__ __host__ __forceinline__ uint64_t source_slice(uint64_t p, uint32_t X
     return st * T + i * X + j;
 }
 
+// Unsigned 32-bit division by a divisor that is fixed for a whole launch: one
+// multiply-high, two shifts and two adds instead of the long division sequence
+// (round-up multiplier method: with l = ceil(log2 d), m = floor(2^32 (2^l - d) / d) + 1,
+// x / d = (t + ((x - t) >> min(l, 1))) >> max(l - 1, 0) where t = mulhi(m, x)).
+// Every wave maps its index to (slice, tile) and the slice to its source with these.
+struct FastDiv {
+    uint32_t d, mul, sh1, sh2;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    FastDiv f;
+    f.d = d;
+    f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l > 1 ? l - 1 : 0;
+    return f;
+}
+
+__device__ __host__ __forceinline__ uint32_t fast_div(uint32_t x, const FastDiv& f)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t t = __umulhi(x, f.mul);
+#else
+    const uint32_t t = (uint32_t)(((uint64_t)x * f.mul) >> 32);
+#endif
+    return (t + ((x - t) >> f.sh1)) >> f.sh2;
+}
+
+// source_slice for indices below 2^32, with the divisions by T = X*Y and by Y prepared
+__device__ __host__ __forceinline__ uint64_t source_slice32(uint32_t p, uint32_t X, const FastDiv& byT,
+                                                            const FastDiv& byY)
+{
+    const uint32_t st = fast_div(p, byT), w = p - st * byT.d;
+    const uint32_t j = fast_div(w, byY), i = w - j * byY.d;
+    return (uint64_t)st * byT.d + (uint64_t)i * X + j;
+}
+
 // ---------------------------------------------------------------------------
 // quantize (qwz_quantize, qgz_reorder): power-of-two block sizes
 // ---------------------------------------------------------------------------
@@ -343,19 +383,20 @@ __device__ __host__ __forceinline__ uint64_t source_slice(uint64_t p, uint32_t X
 template <int DT, int BITS, int LOG2B, int V>
 __global__ __launch_bounds__(kThreads) ZPP_QUANT_OCC void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                                        float* __restrict__ scales, uint64_t L,
-                                                       uint64_t tiles_per_slice, uint64_t total_tiles,
-                                                       uint32_t X, uint32_t Y, int xcd_shift)
+                                                       FastDiv by_tiles_per_slice, uint32_t total_tiles,
+                                                       uint32_t X, FastDiv byT, FastDiv byY, int xcd_shift)
 {
     constexpr int B = 1 << LOG2B;
     constexpr int TILE = 512 * V;
     const int lane = threadIdx.x & (kWave - 1);
     const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wid >= total_tiles) return;
-    const uint64_t p = wid / tiles_per_slice, t = wid % tiles_per_slice;
-    const uint64_t src = (X == 1 || Y == 1) ? p : source_slice(p, X, Y);
-    const uint64_t in_base = src * L + t * TILE;
-    const uint64_t out_base = p * L + t * TILE;
-    const uint64_t rem = L - t * TILE;  // elements of this slice from the tile start on (>= 1)
+    const uint32_t p = fast_div((uint32_t)wid, by_tiles_per_slice);
+    const uint32_t t = (uint32_t)wid - p * by_tiles_per_slice.d;
+    const uint64_t src = (X == 1 || byY.d == 1) ? p : source_slice32(p, X, byT, byY);
+    const uint64_t in_base = src * L + (uint64_t)t * TILE;
+    const uint64_t out_base = (uint64_t)p * L + (uint64_t)t * TILE;
+    const uint64_t rem = L - (uint64_t)t * TILE;  // elements of this slice from the tile start on (>= 1)
 
     float f[V][8];
     bool ok[V];
@@ -848,8 +889,10 @@ int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t
     const uint64_t tiles = tps * slices;
     int xcd_shift;
     const uint64_t grid = plan_grid((tiles + kWavesPerWG - 1) / kWavesPerWG, xcd_shift);
-    if (grid > kMaxGrid) return ZPP_EINVAL;
-    k_quantize<DT, BITS, LOG2B, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, tps, tiles, X, Y, xcd_shift);
+    if (grid > kMaxGrid || tiles >= (1ull << 32) || slices >= (1ull << 32)) return ZPP_EINVAL;
+    k_quantize<DT, BITS, LOG2B, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+        x, codes, scales, L, make_fastdiv((uint32_t)tps), (uint32_t)tiles, X, make_fastdiv(X * Y), make_fastdiv(Y),
+        xcd_shift);
     return launch_status();
 }
 
@@ -965,6 +1008,9 @@ const char* zpp_strerror(int code)
 long long zpp_reorder_source_slice(long long p, int X, int Y, int S)
 {
     if (X < 1 || Y < 1 || S < 1 || p < 0 || p >= (long long)X * Y * S) return -1;
+    if ((long long)X * Y * S < (1ll << 32))  // the same arithmetic the kernels use
+        return (long long)source_slice32((uint32_t)p, (uint32_t)X, make_fastdiv((uint32_t)X * (uint32_t)Y),
+                                         make_fastdiv((uint32_t)Y));
     return (long long)source_slice((uint64_t)p, (uint32_t)X, (uint32_t)Y);
 }
 
@@ -972,6 +1018,9 @@ long long zpp_reorder_mapped_slice(long long pid, int X, int Y, int S)
 {
     if (X < 1 || Y < 1 || S < 1 || pid < 0 || pid >= (long long)X * Y * S) return -1;
     // inverse permutation: the same transpose with the roles of X and Y exchanged
+    if ((long long)X * Y * S < (1ll << 32))
+        return (long long)source_slice32((uint32_t)pid, (uint32_t)Y, make_fastdiv((uint32_t)X * (uint32_t)Y),
+                                         make_fastdiv((uint32_t)X));
     return (long long)source_slice((uint64_t)pid, (uint32_t)Y, (uint32_t)X);
 }
 

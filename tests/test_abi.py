@@ -67,3 +67,20 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.qgz_reorder(fake, 0, 4096, 8, 3, 1, 256, 4, fake, fake, None) == -1
     assert L.qgz_reorder(fake, 0, 0, 8, 3, 1, 256, 4, fake, fake, None) == 0  # empty: no-op
     assert L.qwz_quantize(None, 0, 0, 32, 8, None, None, None) == 0
+
+
+def test_reorder_helpers_equal_oracle_on_many_shapes():
+    """The host helpers share the kernels' index arithmetic (divisions by launch constants
+    done with a multiply-high); compare with the oracle's plain divisions."""
+    import random
+    import oracle
+    rng = random.Random(5)
+    shapes = [(1, 1, 1), (2, 2, 1), (8, 48, 1), (8, 64, 2), (16, 24, 3), (3, 5, 7), (7, 1, 4), (1, 9, 2),
+              (64, 1000, 3), (65535, 3, 2), (5, 65535, 1), (255, 257, 9), (1024, 1024, 4), (65535, 65535, 1)]
+    shapes += [(rng.randint(1, 300), rng.randint(1, 300), rng.randint(1, 5)) for _ in range(40)]
+    for X, Y, S in shapes:
+        total = X * Y * S
+        ps = {0, total - 1, total // 2, X * Y - 1, min(total - 1, X * Y)} | {rng.randrange(total) for _ in range(200)}
+        for p in ps:
+            assert zpp.reorder_source_slice(p, X, Y, S) == oracle.reorder_source_slice(p, X, Y, S), (X, Y, S, p)
+            assert zpp.reorder_mapped_slice(p, X, Y, S) == oracle.reorder_mapped_slice(p, X, Y, S), (X, Y, S, p)
