@@ -22,8 +22,12 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // 16-byte loads a wave issues per tile before it starts computing (tuning knobs)
-#ifndef ZPP_QUANT_V
-#define ZPP_QUANT_V 4
+// (measured best: two for int8 output, four for int4 output, whose stores are narrower)
+#ifndef ZPP_QUANT_V8
+#define ZPP_QUANT_V8 2
+#endif
+#ifndef ZPP_QUANT_V4
+#define ZPP_QUANT_V4 4
 #endif
 #ifndef ZPP_DEQ_V
 #define ZPP_DEQ_V 2
@@ -34,6 +38,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #endif
 #ifndef ZPP_RED_PREFETCH
 #define ZPP_RED_PREFETCH true
+#endif
+// qgz_intra_reduce: preferred code dwords a lane takes per peer (1, 2 or 4)
+#ifndef ZPP_INTRA_NW
+#define ZPP_INTRA_NW 4
 #endif
 // qgz_inter_reduce: code dwords a lane takes per peer (1, 2 or 4)
 #ifndef ZPP_INTER_NW
@@ -711,14 +719,14 @@ __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t
     }
 }
 
-// qgz_intra_reduce, power-of-two blocks with EPL <= B <= 64*EPL: a lane owns EPL
-// consecutive output elements, B/EPL lanes form a block.
-template <int BITS, int LOG2B>
+// qgz_intra_reduce, power-of-two blocks with EPL <= B <= 64*EPL: a lane owns the EPL
+// consecutive output elements of NW code dwords, B/EPL lanes form a block.
+template <int BITS, int LOG2B, int NW>
 __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, int K, uint64_t m,
                                                            uint8_t* __restrict__ codes_out,
                                                            float* __restrict__ scales_out)
 {
-    constexpr int E = EPL<BITS>::value;
+    constexpr int E = EPL<BITS, NW>::value;
     constexpr int B = 1 << LOG2B;
     constexpr int G = B / E;
     static_assert(G >= 1 && G <= kWave, "block must fit a wave");
@@ -728,7 +736,7 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
     const bool ok = e < m;  // m % B == 0 and B % E == 0: a lane is all in or all out
     float acc[E];
     if (ok) {
-        reduce_peers<BITS, 4, ZPP_RED_U, ZPP_RED_PREFETCH>(P, K, e, e >> LOG2B, acc);
+        reduce_peers<BITS, NW, ZPP_RED_U, ZPP_RED_PREFETCH>(P, K, e, e >> LOG2B, acc);
     } else {
 #pragma unroll
         for (int i = 0; i < E; ++i) acc[i] = 0.0f;
@@ -741,13 +749,20 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
     block_scale<BITS>(a, scale, inv);
     if (!ok) return;
     if ((lane & (G - 1)) == 0) scales_out[e >> LOG2B] = scale;
-    u32x4 o;
     constexpr int FIELDS = 32 / BITS;
-    o.x = pack_dword<BITS>(acc, inv);
-    o.y = pack_dword<BITS>(acc + FIELDS, inv);
-    o.z = pack_dword<BITS>(acc + 2 * FIELDS, inv);
-    o.w = pack_dword<BITS>(acc + 3 * FIELDS, inv);
-    st_stream(o, reinterpret_cast<u32x4*>(codes_out + e * BITS / 8));
+    uint32_t o[NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) o[j] = pack_dword<BITS>(acc + j * FIELDS, inv);
+    uint8_t* dst = codes_out + e * BITS / 8;
+    if constexpr (NW == 4) {
+        const u32x4 v = {o[0], o[1], o[2], o[3]};
+        st_stream(v, reinterpret_cast<u32x4*>(dst));
+    } else if constexpr (NW == 2) {
+        const u32x2 v = {o[0], o[1]};
+        st_stream(v, reinterpret_cast<u32x2*>(dst));
+    } else {
+        st_stream(o[0], reinterpret_cast<uint32_t*>(dst));
+    }
 }
 
 // qgz_intra_reduce for any other block size: one wave per block, the sums wait in
@@ -884,7 +899,8 @@ template <int DT, int BITS, int LOG2B>
 int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t L, uint64_t slices, uint32_t X,
                           uint32_t Y, hipStream_t st)
 {
-    constexpr int V = (1 << LOG2B) / 512 > ZPP_QUANT_V ? (1 << LOG2B) / 512 : ZPP_QUANT_V;
+    constexpr int VMIN = BITS == 8 ? ZPP_QUANT_V8 : ZPP_QUANT_V4;
+    constexpr int V = (1 << LOG2B) / 512 > VMIN ? (1 << LOG2B) / 512 : VMIN;
     const uint64_t tps = (L + 512 * V - 1) / (512 * V);
     const uint64_t tiles = tps * slices;
     int xcd_shift;
@@ -934,35 +950,50 @@ int dispatch_quantize(const void* x, int dtype, int bits, uint8_t* codes, float*
 #undef ZPP_Q
 }
 
+template <int BITS, int NW>
+int launch_intra_nw(const PeerTable& P, int K, uint64_t m, int l2, uint8_t* codes_out, float* scales_out,
+                    hipStream_t st)
+{
+    constexpr int E = EPL<BITS, NW>::value;
+    const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
+    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+#define ZPP_I(L2)                                                                                                    \
+    case L2:                                                                                                         \
+        if constexpr ((1 << L2) >= E && (1 << L2) <= kWave * E) {                                                    \
+            k_intra_reduce<BITS, L2, NW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out); \
+            return launch_status();                                                                                  \
+        }                                                                                                            \
+        return ZPP_EINVAL
+    switch (l2) {
+        ZPP_I(5);
+        ZPP_I(6);
+        ZPP_I(7);
+        ZPP_I(8);
+        ZPP_I(9);
+        ZPP_I(10);
+        ZPP_I(11);
+    default: return ZPP_EINVAL;
+    }
+#undef ZPP_I
+}
+
 template <int BITS>
 int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* codes_out, float* scales_out,
                  hipStream_t st)
 {
-    constexpr int E = EPL<BITS>::value;
     const int l2 = log2_or_neg(B);
-    const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
-    const uint64_t grid = ((waves + kWavesPerWG - 1) / kWavesPerWG);
-    if (grid > kMaxGrid || m / B > kMaxGrid) return ZPP_EINVAL;
-#define ZPP_I(L2)                                                                                               \
-    case L2:                                                                                                    \
-        k_intra_reduce<BITS, L2><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out); \
-        return launch_status()
-    if (l2 >= 0 && (int)B >= E && (int)B <= kWave * E) {
-        switch (l2) {
-            ZPP_I(5);
-            ZPP_I(6);
-            ZPP_I(7);
-            ZPP_I(8);
-            ZPP_I(9);
-            ZPP_I(10);
-        default: break;
-        }
-        if (BITS == 4 && l2 == 11) {
-            k_intra_reduce<BITS, (BITS == 4 ? 11 : 10)><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out);
-            return launch_status();
+    if (m / B > kMaxGrid) return ZPP_EINVAL;
+    if (l2 >= 0) {
+        // fewest code dwords per lane (most waves) for which a block still fits one wave
+        int nw = ZPP_INTRA_NW;
+        while (nw < 4 && B > (uint32_t)(kWave * nw * 32 / BITS)) nw <<= 1;
+        if (B <= (uint32_t)(kWave * nw * 32 / BITS)) {
+            if (nw == 1) return launch_intra_nw<BITS, 1>(P, K, m, l2, codes_out, scales_out, st);
+            if (nw == 2) return launch_intra_nw<BITS, 2>(P, K, m, l2, codes_out, scales_out, st);
+            return launch_intra_nw<BITS, 4>(P, K, m, l2, codes_out, scales_out, st);
         }
     }
-#undef ZPP_I
     k_intra_reduce_anyblock<BITS><<<dim3((uint32_t)(m / B)), dim3(kWave), 0, st>>>(P, K, B, codes_out, scales_out);
     return launch_status();
 }

@@ -320,3 +320,52 @@ def test_one_layer_of_the_benchmark_step_hidden_12288():
                   for i in range(Y - 1)]
         oo = oracle.qgz_inter_reduce([c1] + [c for c, _ in others], [s1] + [s for _, s in others], GB, GB, 4, float(W))
         assert np.array_equal(dev_bytes(out[ob * GB:(ob + 1) * GB]), oo.view(np.uint8))
+
+
+# ----------------------------------------------------------------------------
+# a single tensor of more than 2^32 elements: 64-bit element offsets everywhere
+# ----------------------------------------------------------------------------
+
+def test_single_tensor_beyond_32_bit_offsets():
+    B = 2048
+    n = (1 << 32) + 3 * B * 1001            # 4.3e9 elements, ragged against every tile size
+    x = workloads.weights(n, device=DEV, tensor_id=77)
+    codes, scales = zpp.qwz_quantize(x, B, 8)
+    y = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    zpp.qwz_dequantize(codes, scales, n, B, 8, out=y)
+    torch.cuda.synchronize()
+    # every element, torch route, in pieces to bound the temporaries
+    piece = B << 18
+    for lo in range(0, n, piece):
+        hi = min(lo + piece, n)
+        q, sc = torch_codes(x[lo:hi], B, 8)
+        assert torch.equal(scales[lo // B:hi // B].view(torch.int32), sc.view(torch.int32)), lo
+        assert torch.equal(codes[lo:hi].view(torch.int8), q), lo
+        want = (q.float().view(-1, B) * sc[:, None]).view(-1).to(torch.bfloat16)
+        assert torch.equal(y[lo:hi].view(torch.int16), want.view(torch.int16)), lo
+        del q, sc, want
+    nb = n // B
+    for b in sample_blocks(nb, 12, seed=11, always=(0, nb - 1, (1 << 32) // B - 1, (1 << 32) // B, (1 << 31) // B)):
+        oc, os_ = oracle.qwz_quantize(bits_of(x[b * B:(b + 1) * B]), oracle.BF16, B, 8)
+        assert np.array_equal(dev_bytes(codes[b * B:(b + 1) * B]), oc)
+        assert np.array_equal(dev_bytes(scales[b:b + 1]), os_.view(np.uint8))
+        assert np.array_equal(dev_bytes(y[b * B:(b + 1) * B]),
+                              oracle.qwz_dequantize(oc, os_, B, B, 8, oracle.BF16).view(np.uint8))
+    # the gradient path on the same scale: reorder of 4.3e9 fp16 elements, X = 8, Y = 48
+    del codes, scales, y
+    g = x.view(torch.float16)               # reinterpret the bits: any finite pattern is a valid input
+    g = torch.nan_to_num(g, nan=0.0, posinf=1.0, neginf=-1.0)
+    X, Y, GB = 8, 48, 512
+    n2 = (n // (X * Y * GB)) * (X * Y * GB)
+    g = g[:n2]
+    L = n2 // (X * Y)
+    gc, gs = zpp.qgz_reorder(g, X, Y, 1, GB, 4)
+    torch.cuda.synchronize()
+    bps = L // GB
+    for ob in sample_blocks(n2 // GB, 16, seed=12, always=(0, n2 // GB - 1, (1 << 32) // GB, (1 << 32) // GB - 1)):
+        p, rb = divmod(ob, bps)
+        src = oracle.reorder_source_slice(p, X, Y, 1)
+        lo = src * L + rb * GB
+        oc, os_ = oracle.qwz_quantize(bits_of(g[lo:lo + GB]), oracle.F16, GB, 4)
+        assert np.array_equal(dev_bytes(gc[ob * GB // 2:(ob + 1) * GB // 2]), oc)
+        assert np.array_equal(dev_bytes(gs[ob:ob + 1]), os_.view(np.uint8))
