@@ -32,6 +32,12 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef ZPP_DEQ_V
 #define ZPP_DEQ_V 2
 #endif
+// quantize: loads a wave keeps in flight (0 = all of the tile's).  One measured best: with
+// eight waves per SIMD that already covers the bandwidth-delay product, and more bytes
+// in flight only queue up in the memory system (-7 % with all four loads outstanding).
+#ifndef ZPP_QUANT_INFLIGHT
+#define ZPP_QUANT_INFLIGHT 1
+#endif
 // reduce stages: peers fetched per group, and whether the next group is fetched ahead
 #ifndef ZPP_RED_U
 #define ZPP_RED_U 4
@@ -388,36 +394,29 @@ __device__ __host__ __forceinline__ uint64_t source_slice32(uint32_t p, uint32_t
 // >= 512 elements span B/512 loads (maximum folded across registers, then across
 // the wave); smaller blocks sit inside one load, B/8 lanes each.
 
-template <int DT, int BITS, int LOG2B, int V>
-__global__ __launch_bounds__(kThreads) ZPP_QUANT_OCC void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
-                                                       float* __restrict__ scales, uint64_t L,
-                                                       FastDiv by_tiles_per_slice, uint32_t total_tiles,
-                                                       uint32_t X, FastDiv byT, FastDiv byY, int xcd_shift)
+// One tile.  FULL: the whole tile lies inside the slice, so no lane is masked and the
+// V loads go out back to back; otherwise lanes past the end of the slice are masked.
+template <int DT, int BITS, int LOG2B, int V, bool FULL>
+__device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_t* __restrict__ codes,
+                                              float* __restrict__ scales, uint64_t in_base, uint64_t out_base,
+                                              uint64_t rem, int lane)
 {
     constexpr int B = 1 << LOG2B;
-    constexpr int TILE = 512 * V;
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (wid >= total_tiles) return;
-    const uint32_t p = fast_div((uint32_t)wid, by_tiles_per_slice);
-    const uint32_t t = (uint32_t)wid - p * by_tiles_per_slice.d;
-    const uint64_t src = (X == 1 || byY.d == 1) ? p : source_slice32(p, X, byT, byY);
-    const uint64_t in_base = src * L + (uint64_t)t * TILE;
-    const uint64_t out_base = (uint64_t)p * L + (uint64_t)t * TILE;
-    const uint64_t rem = L - (uint64_t)t * TILE;  // elements of this slice from the tile start on (>= 1)
-
     float f[V][8];
     bool ok[V];
 #pragma unroll
     for (int k = 0; k < V; ++k) {
         const uint32_t off = (uint32_t)(k * kWave + lane) * 8u;
-        ok[k] = off < rem;
+        ok[k] = FULL || off < rem;
         if (ok[k]) {
             load8<DT>(x, in_base + off, f[k]);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) f[k][i] = 0.0f;
         }
+#if ZPP_QUANT_INFLIGHT > 0
+        if ((k + 1) % ZPP_QUANT_INFLIGHT == 0) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+#endif
     }
 
     if constexpr (B >= 512) {
@@ -452,6 +451,28 @@ __global__ __launch_bounds__(kThreads) ZPP_QUANT_OCC void k_quantize(const void*
             }
         }
     }
+}
+
+template <int DT, int BITS, int LOG2B, int V>
+__global__ __launch_bounds__(kThreads) ZPP_QUANT_OCC void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
+                                                       float* __restrict__ scales, uint64_t L,
+                                                       FastDiv by_tiles_per_slice, uint32_t total_tiles,
+                                                       uint32_t X, FastDiv byT, FastDiv byY, int xcd_shift)
+{
+    constexpr int TILE = 512 * V;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wid >= total_tiles) return;
+    const uint32_t p = fast_div((uint32_t)wid, by_tiles_per_slice);
+    const uint32_t t = (uint32_t)wid - p * by_tiles_per_slice.d;
+    const uint64_t src = (X == 1 || byY.d == 1) ? p : source_slice32(p, X, byT, byY);
+    const uint64_t in_base = src * L + (uint64_t)t * TILE;
+    const uint64_t out_base = (uint64_t)p * L + (uint64_t)t * TILE;
+    const uint64_t rem = L - (uint64_t)t * TILE;  // elements of this slice from the tile start on (>= 1)
+    if (rem >= TILE)
+        quantize_tile<DT, BITS, LOG2B, V, true>(x, codes, scales, in_base, out_base, rem, lane);
+    else
+        quantize_tile<DT, BITS, LOG2B, V, false>(x, codes, scales, in_base, out_base, rem, lane);
 }
 
 // Any block size that is a multiple of 32 (not a power of two, or larger than the
