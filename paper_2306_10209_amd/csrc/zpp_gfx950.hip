@@ -533,19 +533,14 @@ __device__ __forceinline__ float byte_f32(uint32_t w, int i)
 // loads issued first.  The writes are two thirds of the traffic, so they get the
 // full-width contiguous stores.
 
-template <int ODT, int BITS, int V>
-__global__ __launch_bounds__(kThreads) ZPP_DEQ_OCC void k_dequantize(const uint8_t* __restrict__ codes,
-                                                         const float* __restrict__ scales,
-                                                         void* __restrict__ y, uint64_t n, uint32_t B,
-                                                         int log2b /* -1: not a power of two */, int xcd_shift)
+// One tile of qwz_dequantize.  Lanes past the end of the tensor are masked; the masked
+// form is kept for full tiles too: it issues each 16-byte store as soon as its eight
+// values are ready, which measured 2 % faster than an unmasked variant that stored last.
+template <int ODT, int BITS, int V, bool POW2>
+__device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ codes, const float* __restrict__ scales,
+                                                void* __restrict__ y, uint64_t base, uint64_t rem, uint32_t B,
+                                                int log2b, int lane)
 {
-    constexpr int TILE = 512 * V;
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t base = wid * TILE;
-    if (base >= n) return;
-    const uint64_t rem = n - base;
-
     uint32_t w[V][2];
     float s[V];
     bool ok[V];
@@ -564,7 +559,7 @@ __global__ __launch_bounds__(kThreads) ZPP_DEQ_OCC void k_dequantize(const uint8
             } else {
                 w[k][0] = ld_stream(reinterpret_cast<const uint32_t*>(codes + (e >> 1)));
             }
-            const uint64_t blk = log2b >= 0 ? (e >> log2b) : (e / B);
+            const uint64_t blk = POW2 ? (e >> log2b) : (e / B);
             s[k] = scales[blk];
         }
     }
@@ -597,6 +592,20 @@ __global__ __launch_bounds__(kThreads) ZPP_DEQ_OCC void k_dequantize(const uint8
             st_stream(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(y) + e));
         }
     }
+}
+
+template <int ODT, int BITS, int V, bool POW2>
+__global__ __launch_bounds__(kThreads) ZPP_DEQ_OCC void k_dequantize(const uint8_t* __restrict__ codes,
+                                                         const float* __restrict__ scales,
+                                                         void* __restrict__ y, uint64_t n, uint32_t B,
+                                                         int log2b /* used when POW2 */, int xcd_shift)
+{
+    constexpr int TILE = 512 * V;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t base = wid * TILE;
+    if (base >= n) return;
+    dequantize_tile<ODT, BITS, V, POW2>(codes, scales, y, base, n - base, B, log2b, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -1112,7 +1121,13 @@ int qwz_dequantize(const void* codes, const float* scales, size_t n, int block, 
     const uint8_t* c = static_cast<const uint8_t*>(codes);
     const int l2 = log2_or_neg((uint32_t)block);
     hipStream_t st = static_cast<hipStream_t>(stream);
-#define ZPP_D(ODT, BITS) k_dequantize<ODT, BITS, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift)
+#define ZPP_D(ODT, BITS)                                                                                          \
+    do {                                                                                                          \
+        if (l2 >= 0)                                                                                              \
+            k_dequantize<ODT, BITS, V, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift);  \
+        else                                                                                                      \
+            k_dequantize<ODT, BITS, V, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift); \
+    } while (0)
     if (bits == 8) {
         if (out_dtype == ZPP_F16) ZPP_D(ZPP_F16, 8);
         else if (out_dtype == ZPP_BF16) ZPP_D(ZPP_BF16, 8);
