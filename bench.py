@@ -369,6 +369,21 @@ def per_config_kernels(torch, zpp, workloads, dev):
 
     run("cfg1.qwz_quantize_32_shards", Bytes.quantize(n_total, B, 8), quantize_layer,
         "32 launches (8 rank shards x 4 matrices) written at their offsets of the gather buffer", batch=2)
+    # the 8 simulated ranks are independent: the same 32 launches spread over 4 streams
+    streams = [torch.cuda.Stream(device=dev) for _ in range(4)]
+
+    def quantize_layer_streams():
+        main = torch.cuda.current_stream(dev)
+        for st in streams:
+            st.wait_stream(main)
+        for i, (lo, sh) in enumerate(shards):
+            zpp.qwz_quantize(w[lo:lo + sh], B, 8, codes=codes[lo:lo + sh], scales=scales[lo // B:(lo + sh) // B],
+                             stream=streams[i % 4])
+        for st in streams:
+            main.wait_stream(st)
+
+    run("cfg1.qwz_quantize_32_shards_4_streams", Bytes.quantize(n_total, B, 8), quantize_layer_streams,
+        "as above, launches round-robin on 4 streams so that one shard's tail overlaps the next one's start", batch=2)
     run("cfg1.qwz_dequantize_layer", Bytes.dequantize(n_total, B, 8),
         lambda: zpp.qwz_dequantize(codes, scales, n_total, B, 8, out=w), batch=4)
     del w, codes, scales

@@ -21,8 +21,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// 16-byte loads a wave issues per tile before it starts computing (tuning knobs)
-// (measured best: two for int8 output, four for int4 output, whose stores are narrower)
+// Tuning constants (all measured on MI355X; -D overrides are for experiments).
+//
+// Loads per lane and tile, i.e. a wave's tile is 512 * V elements.  Best: two for int8
+// output and for dequantize, four for int4 output, whose stores are narrower.
 #ifndef ZPP_QUANT_V8
 #define ZPP_QUANT_V8 2
 #endif
@@ -52,24 +54,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // qgz_inter_reduce: code dwords a lane takes per peer (1, 2 or 4)
 #ifndef ZPP_INTER_NW
 #define ZPP_INTER_NW 1
-#endif
-
-// optional cap on resident waves per SIMD for the streaming kernels (0 = none)
-#ifndef ZPP_QUANT_WAVES
-#define ZPP_QUANT_WAVES 0
-#endif
-#ifndef ZPP_DEQ_WAVES
-#define ZPP_DEQ_WAVES 0
-#endif
-#if ZPP_QUANT_WAVES > 0
-#define ZPP_QUANT_OCC __attribute__((amdgpu_waves_per_eu(1, ZPP_QUANT_WAVES)))
-#else
-#define ZPP_QUANT_OCC
-#endif
-#if ZPP_DEQ_WAVES > 0
-#define ZPP_DEQ_OCC __attribute__((amdgpu_waves_per_eu(1, ZPP_DEQ_WAVES)))
-#else
-#define ZPP_DEQ_OCC
 #endif
 
 constexpr int kWave = 64;
@@ -454,7 +438,7 @@ __device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_
 }
 
 template <int DT, int BITS, int LOG2B, int V>
-__global__ __launch_bounds__(kThreads) ZPP_QUANT_OCC void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
+__global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                                        float* __restrict__ scales, uint64_t L,
                                                        FastDiv by_tiles_per_slice, uint32_t total_tiles,
                                                        uint32_t X, FastDiv byT, FastDiv byY, int xcd_shift)
@@ -595,7 +579,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ code
 }
 
 template <int ODT, int BITS, int V, bool POW2>
-__global__ __launch_bounds__(kThreads) ZPP_DEQ_OCC void k_dequantize(const uint8_t* __restrict__ codes,
+__global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restrict__ codes,
                                                          const float* __restrict__ scales,
                                                          void* __restrict__ y, uint64_t n, uint32_t B,
                                                          int log2b /* used when POW2 */, int xcd_shift)
