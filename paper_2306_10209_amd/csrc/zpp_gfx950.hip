@@ -57,7 +57,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #endif
 
 constexpr int kWave = 64;
-constexpr int kWavesPerWG = 4;
+#ifndef ZPP_WAVES_PER_WG
+#define ZPP_WAVES_PER_WG 4
+#endif
+constexpr int kWavesPerWG = ZPP_WAVES_PER_WG;
 constexpr int kThreads = kWave * kWavesPerWG;
 constexpr float kTiny = 0x1p-100f;  // blocks with a smaller maximum are coded as all zero
 
@@ -374,12 +377,15 @@ __device__ __host__ __forceinline__ uint64_t source_slice32(uint32_t p, uint32_t
 //
 // A wave owns a tile of 512*V consecutive elements of one output slice; load k of
 // lane l covers elements (k*64 + l)*8 .. +8, so every wave-wide load or store is
-// one contiguous run.  All V loads are issued before the first use.  Blocks of
-// >= 512 elements span B/512 loads (maximum folded across registers, then across
-// the wave); smaller blocks sit inside one load, B/8 lanes each.
+// one contiguous run.  Blocks of >= 512 elements span B/512 loads (maximum folded
+// across registers, then across the wave); smaller blocks sit inside one load, B/8
+// lanes each.  The un-quantized values of a block stay in registers between the
+// maximum and the encode (Sec. 4.2), so the tensor is read exactly once.
 
-// One tile.  FULL: the whole tile lies inside the slice, so no lane is masked and the
-// V loads go out back to back; otherwise lanes past the end of the slice are masked.
+// One tile.  FULL: the whole tile lies inside the slice, so no lane is masked;
+// otherwise lanes past the end of the slice are masked.  A wave waits for each load
+// before it issues the next (ZPP_QUANT_INFLIGHT): the other waves of the SIMD keep
+// the memory system busy.
 template <int DT, int BITS, int LOG2B, int V, bool FULL>
 __device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                               float* __restrict__ scales, uint64_t in_base, uint64_t out_base,
