@@ -41,7 +41,7 @@ def parse():
                     help="skip the timings of the Sec. 4.1 launch schedules (pipeline stages, weight prefetch)")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the per-kernel timings at the shapes of the other configurations")
-    ap.add_argument("--cpu-sample-div", type=int, default=4,
+    ap.add_argument("--cpu-sample-div", type=int, default=1,
                     help="the CPU oracle is timed on 1/div of one layer")
     return ap.parse_args()
 
