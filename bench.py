@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9   # plain (unpacked) vector-ALU lane-operations per second
 METRIC = "effective HBM GB/s (and % of peak) per qwZ/qgZ kernel at 1 MI355X"
 
 
@@ -191,6 +192,16 @@ def main():
     for _ in range(2):
         step("all")
     torch.cuda.synchronize()
+    # vector-ALU instructions per launch measured with rocprofv3 --pmc SQ_INSTS_VALU (committed
+    # summary); one wave64 instruction is 64 lane-operations, the chip retires 256 CUs x 4 SIMDs x
+    # 16 lanes x 2.4 GHz = 39.3e12 of them per second
+    valu = {}
+    vpath = os.path.join(ROOT, "profiles", "bench_step_valu.txt")
+    if os.path.exists(vpath):
+        for line in open(vpath):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "VALU":
+                valu[parts[1]] = int(parts[2].split("=")[1])
     kernels = {}
     for k, ev in events.items():
         ms = [a.elapsed_time(b) for a, b in ev]
@@ -199,6 +210,10 @@ def main():
         kernels[k] = {"bytes": bytes_per[k], "avg_ms": round(avg, 5), "min_ms": round(min(ms), 5),
                       "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
                       "launches": len(ms)}
+        if k in valu:
+            alu = valu[k] * 64 / (avg * 1e-3)
+            kernels[k]["frac_of_alu_peak"] = round(alu / ALU_PEAK_LANE_OPS, 4)
+            kernels[k]["bound"] = "alu" if alu / ALU_PEAK_LANE_OPS > gbs / HBM_PEAK_GBS else "hbm"
 
     # measured copy ceiling: 2 GiB read + 2 GiB written per launch
     src = grad.view(torch.uint8)[: 1 << 31]
