@@ -639,6 +639,11 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 // exact value (u-8)*s = q*s rounded once, because s*2^24, s*2^20 and 8*s are exact
 // (power-of-two factors, s < 2^100 checked by the caller).  The conversion of the
 // binary16 operand happens inside the mixed-precision fma instruction.
+//
+// FIRST: the accumulator is set instead of added to.  The sum starts from +0 and a decoded
+// value is never -0 (code 0 gives 8s - 8s = +0, a zero scale gives +0 + -0 = +0), so
+// 0 + d and d are the same bits and the first peer needs neither the zeroing nor the add.
+template <bool FIRST>
 __device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w, float s_lo, float s_hi,
                                              float bias)
 {
@@ -648,36 +653,42 @@ __device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w
     const f16x2 b = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(w, 0x88888888u, 0x00F000F0u, 0x28));  // elements 1, 5
     const f16x2 c = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(v, 0x88888888u, 0x000F000Fu, 0x28));  // elements 2, 6
     const f16x2 d = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(v, 0x88888888u, 0x00F000F0u, 0x28));  // elements 3, 7
-    acc[0] = acc[0] + __builtin_fmaf((float)a.x, s_lo, bias);
-    acc[1] = acc[1] + __builtin_fmaf((float)b.x, s_hi, bias);
-    acc[2] = acc[2] + __builtin_fmaf((float)c.x, s_lo, bias);
-    acc[3] = acc[3] + __builtin_fmaf((float)d.x, s_hi, bias);
-    acc[4] = acc[4] + __builtin_fmaf((float)a.y, s_lo, bias);
-    acc[5] = acc[5] + __builtin_fmaf((float)b.y, s_hi, bias);
-    acc[6] = acc[6] + __builtin_fmaf((float)c.y, s_lo, bias);
-    acc[7] = acc[7] + __builtin_fmaf((float)d.y, s_hi, bias);
+    acc[0] = FIRST ? __builtin_fmaf((float)a.x, s_lo, bias) : acc[0] + __builtin_fmaf((float)a.x, s_lo, bias);
+    acc[1] = FIRST ? __builtin_fmaf((float)b.x, s_hi, bias) : acc[1] + __builtin_fmaf((float)b.x, s_hi, bias);
+    acc[2] = FIRST ? __builtin_fmaf((float)c.x, s_lo, bias) : acc[2] + __builtin_fmaf((float)c.x, s_lo, bias);
+    acc[3] = FIRST ? __builtin_fmaf((float)d.x, s_hi, bias) : acc[3] + __builtin_fmaf((float)d.x, s_hi, bias);
+    acc[4] = FIRST ? __builtin_fmaf((float)a.y, s_lo, bias) : acc[4] + __builtin_fmaf((float)a.y, s_lo, bias);
+    acc[5] = FIRST ? __builtin_fmaf((float)b.y, s_hi, bias) : acc[5] + __builtin_fmaf((float)b.y, s_hi, bias);
+    acc[6] = FIRST ? __builtin_fmaf((float)c.y, s_lo, bias) : acc[6] + __builtin_fmaf((float)c.y, s_lo, bias);
+    acc[7] = FIRST ? __builtin_fmaf((float)d.y, s_hi, bias) : acc[7] + __builtin_fmaf((float)d.y, s_hi, bias);
 }
 
 // acc[i] += decode(code_i, s) for the codes of NW dwords, in place
-template <int BITS, int NW>
+template <int BITS, int NW, bool FIRST>
 __device__ __forceinline__ void accumulate(float (&acc)[(EPL<BITS, NW>::value)], const uint32_t (&d)[NW], float s)
 {
     if (BITS == 4) {
         if (s < 0x1p100f) {
             const float s_lo = s * 0x1p24f, s_hi = s * 0x1p20f, bias = s * -8.0f;
 #pragma unroll
-            for (int j = 0; j < NW; ++j) add_nibbles8(acc + j * 8, d[j], s_lo, s_hi, bias);
+            for (int j = 0; j < NW; ++j) add_nibbles8<FIRST>(acc + j * 8, d[j], s_lo, s_hi, bias);
         } else {  // scales this large never come from 16-bit gradients; plain convert and multiply
 #pragma unroll
             for (int j = 0; j < NW; ++j)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[j * 8 + i] = acc[j * 8 + i] + nibble_f32(d[j], i) * s;
+                for (int i = 0; i < 8; ++i) {
+                    const float v = nibble_f32(d[j], i) * s;  // int -> float never gives -0
+                    acc[j * 8 + i] = FIRST ? v : acc[j * 8 + i] + v;
+                }
         }
     } else {
 #pragma unroll
         for (int j = 0; j < NW; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[j * 4 + i] = acc[j * 4 + i] + byte_f32(d[j], i) * s;
+            for (int i = 0; i < 4; ++i) {
+                const float v = byte_f32(d[j], i) * s;
+                acc[j * 4 + i] = FIRST ? v : acc[j * 4 + i] + v;
+            }
     }
 }
 
@@ -692,50 +703,56 @@ __device__ __forceinline__ void load_group(const PeerTable& P, int k0, uint64_t 
     }
 }
 
-template <int BITS, int NW, int U>
+// FIRST: w[0] is the very first peer of the sum
+template <int BITS, int NW, int U, bool FIRST>
 __device__ __forceinline__ void add_group(float (&acc)[(EPL<BITS, NW>::value)], const uint32_t (&w)[U][NW],
                                           const float (&s)[U])
 {
+    accumulate<BITS, NW, FIRST>(acc, w[0], s[0]);
 #pragma unroll
-    for (int u = 0; u < U; ++u) accumulate<BITS, NW>(acc, w[u], s[u]);
+    for (int u = 1; u < U; ++u) accumulate<BITS, NW, false>(acc, w[u], s[u]);
 }
 
-// Sum of the K peers' decoded values for the EPL elements starting at element e.
+// Sum of the K >= 1 peers' decoded values for the EPL elements starting at element e.
 // Peers are added in ascending order.  They are fetched in groups of U; with
 // PREFETCH the next group's loads are issued before the current group is decoded.
 template <int BITS, int NW, int U, bool PREFETCH>
 __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t e, uint64_t blk,
                                              float (&acc)[(EPL<BITS, NW>::value)])
 {
-#pragma unroll
-    for (int i = 0; i < EPL<BITS, NW>::value; ++i) acc[i] = 0.0f;
     const uint64_t byte_off = e * BITS / 8;
     const int full = K / U;
-    if constexpr (PREFETCH) {
+    int k = 0;  // peers done
+    if (full > 0) {
         uint32_t wa[U][NW], wb[U][NW];
         float sa[U], sb[U];
-        if (full > 0) load_group<NW, U>(P, 0, byte_off, blk, wa, sa);
-        int g = 0;
-        for (; g + 2 <= full; g += 2) {
-            load_group<NW, U>(P, (g + 1) * U, byte_off, blk, wb, sb);
-            add_group<BITS, NW, U>(acc, wa, sa);
-            if (g + 2 < full) load_group<NW, U>(P, (g + 2) * U, byte_off, blk, wa, sa);
-            add_group<BITS, NW, U>(acc, wb, sb);
+        load_group<NW, U>(P, 0, byte_off, blk, wa, sa);
+        if (PREFETCH && full > 1) load_group<NW, U>(P, U, byte_off, blk, wb, sb);
+        add_group<BITS, NW, U, true>(acc, wa, sa);
+        // groups 1 .. full-1, alternating between the two register sets
+        for (int g = 1; g < full; g += 2) {
+            if (!PREFETCH) load_group<NW, U>(P, g * U, byte_off, blk, wb, sb);
+            if (PREFETCH && g + 1 < full) load_group<NW, U>(P, (g + 1) * U, byte_off, blk, wa, sa);
+            add_group<BITS, NW, U, false>(acc, wb, sb);
+            if (g + 1 < full) {
+                if (!PREFETCH) load_group<NW, U>(P, (g + 1) * U, byte_off, blk, wa, sa);
+                if (PREFETCH && g + 2 < full) load_group<NW, U>(P, (g + 2) * U, byte_off, blk, wb, sb);
+                add_group<BITS, NW, U, false>(acc, wa, sa);
+            }
         }
-        if (g < full) add_group<BITS, NW, U>(acc, wa, sa);
+        k = full * U;
     } else {
-        for (int g = 0; g < full; ++g) {
-            uint32_t w[U][NW];
-            float sc[U];
-            load_group<NW, U>(P, g * U, byte_off, blk, w, sc);
-            add_group<BITS, NW, U>(acc, w, sc);
-        }
+        uint32_t w1[1][NW];
+        float s1[1];
+        load_group<NW, 1>(P, 0, byte_off, blk, w1, s1);
+        add_group<BITS, NW, 1, true>(acc, w1, s1);
+        k = 1;
     }
-    for (int k = full * U; k < K; ++k) {
+    for (; k < K; ++k) {
         uint32_t w1[1][NW];
         float s1[1];
         load_group<NW, 1>(P, k, byte_off, blk, w1, s1);
-        add_group<BITS, NW, 1>(acc, w1, s1);
+        add_group<BITS, NW, 1, false>(acc, w1, s1);
     }
 }
 
