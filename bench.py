@@ -449,42 +449,63 @@ def per_config_kernels(torch, zpp, workloads, dev):
 
 def cpu_baseline(args, n_L, X, Y, W, WB, WBITS, GB_, GBITS):
     """The CPU oracle, as it stands, on 1/div of one layer pushed through the same
-    six calls a layer costs in a step (2 dequantize, reorder, intra, inter, quantize)."""
+    six calls a layer costs in a step (2 dequantize, reorder, intra, inter, quantize):
+    on all host threads, and on 1/16 of that sample with one thread (whose outputs
+    must be the bytes the threaded run gives for the same sample)."""
     import numpy as np
     import torch
     import oracle
     from paper_2306_10209_amd import workloads
 
-    div = args.cpu_sample_div
-    n = n_L // div
-    assert n % (X * Y * GB_) == 0 and (n // W) % WB == 0
-    m, L = n // X, n // W
-    threads = oracle.set_threads(0)
     gen = "cuda:0" if torch.cuda.is_available() else "cpu"     # drawing the numbers is not part of the baseline
-    w = workloads.as_bits(workloads.weights(n, device=gen, tensor_id=1))
-    wc, ws = oracle.qwz_quantize(w, oracle.BF16, WB, WBITS)
-    g = workloads.as_bits(workloads.gradients(n, device=gen, tensor_id=3, tail_std=0.0))
-    peers = [oracle.qwz_quantize(workloads.as_bits(workloads.gradients(m, device=gen, tensor_id=100 + k, tail_std=0.0)),
-                                 oracle.F16, GB_, GBITS) for k in range(X - 1)]
-    nodes = [oracle.qwz_quantize(workloads.as_bits(workloads.gradients(L, device=gen, tensor_id=200 + i, tail_std=0.0)),
-                                 oracle.F16, GB_, GBITS) for i in range(Y - 1)]
-    own = workloads.as_bits(workloads.weights(L, device=gen, tensor_id=2))
-    t0 = time.perf_counter()
-    oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
-    oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
-    gc, gs = oracle.qgz_reorder(g, oracle.F16, X, Y, 1, GB_, GBITS)
-    ic, isc = oracle.qgz_intra_reduce([gc[:m // 2]] + [p[0] for p in peers], [gs[:m // GB_]] + [p[1] for p in peers],
-                                      m, GB_, GBITS)
-    oracle.qgz_inter_reduce([ic[:L // 2]] + [c for c, _ in nodes], [isc[:L // GB_]] + [s for _, s in nodes],
-                            L, GB_, GBITS, float(W))
-    oracle.qwz_quantize(own, oracle.BF16, WB, WBITS)
-    dt = time.perf_counter() - t0
-    nbytes = (2 * Bytes.dequantize(n, WB, WBITS) + Bytes.quantize(n, GB_, GBITS) + Bytes.intra(m, GB_, GBITS, X)
-              + Bytes.inter(L, GB_, GBITS, Y) + Bytes.quantize(L, WB, WBITS))
-    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": f"1/{div} of one layer ({n} elements) through the six calls a layer costs per step "
-                      f"(= 1/{div * args.layers} of a step), {dt:.1f} s of wall time",
-            "seconds": round(dt, 2)}
+
+    def prepare(n):
+        assert n % (X * Y * GB_) == 0 and (n // W) % WB == 0
+        m, L = n // X, n // W
+        w = workloads.as_bits(workloads.weights(n, device=gen, tensor_id=1))
+        wc, ws = oracle.qwz_quantize(w, oracle.BF16, WB, WBITS)
+        g = workloads.as_bits(workloads.gradients(n, device=gen, tensor_id=3, tail_std=0.0))
+        peers = [oracle.qwz_quantize(workloads.as_bits(workloads.gradients(m, device=gen, tensor_id=100 + k, tail_std=0.0)),
+                                     oracle.F16, GB_, GBITS) for k in range(X - 1)]
+        nodes = [oracle.qwz_quantize(workloads.as_bits(workloads.gradients(L, device=gen, tensor_id=200 + i, tail_std=0.0)),
+                                     oracle.F16, GB_, GBITS) for i in range(Y - 1)]
+        own = workloads.as_bits(workloads.weights(L, device=gen, tensor_id=2))
+        return n, wc, ws, g, peers, nodes, own
+
+    def six(inp):
+        n, wc, ws, g, peers, nodes, own = inp
+        m, L = n // X, n // W
+        t0 = time.perf_counter()
+        y1 = oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
+        oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
+        gc, gs = oracle.qgz_reorder(g, oracle.F16, X, Y, 1, GB_, GBITS)
+        ic, isc = oracle.qgz_intra_reduce([gc[:m // 2]] + [p[0] for p in peers], [gs[:m // GB_]] + [p[1] for p in peers],
+                                          m, GB_, GBITS)
+        out = oracle.qgz_inter_reduce([ic[:L // 2]] + [c for c, _ in nodes], [isc[:L // GB_]] + [s for _, s in nodes],
+                                      L, GB_, GBITS, float(W))
+        qc, qs = oracle.qwz_quantize(own, oracle.BF16, WB, WBITS)
+        dt = time.perf_counter() - t0
+        nbytes = (2 * Bytes.dequantize(n, WB, WBITS) + Bytes.quantize(n, GB_, GBITS) + Bytes.intra(m, GB_, GBITS, X)
+                  + Bytes.inter(L, GB_, GBITS, Y) + Bytes.quantize(L, WB, WBITS))
+        return dt, nbytes, (y1, gc, gs, ic, isc, out, qc, qs)
+
+    div = args.cpu_sample_div
+    threads = oracle.set_threads(0)
+    dt, nbytes, _ = six(prepare(n_L // div))
+    res = {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+           "sample": f"1/{div} of one layer ({n_L // div} elements) through the six calls a layer costs per step "
+                     f"(= 1/{div * args.layers} of a step), {dt:.1f} s of wall time",
+           "seconds": round(dt, 2)}
+    small = prepare(n_L // (16 * div))
+    _, _, threaded = six(small)
+    oracle.set_threads(1)
+    dt1, nbytes1, single = six(small)
+    oracle.set_threads(threads)
+    res["single_thread"] = {"value": round(nbytes1 / dt1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                            "sample": f"1/{16 * div} of one layer ({n_L // (16 * div)} elements), {dt1:.1f} s",
+                            "same_bytes_as_threaded": all(np.array_equal(a.view(np.uint8), b.view(np.uint8))
+                                                          for a, b in zip(threaded, single))}
+    return res
 
 
 if __name__ == "__main__":

@@ -1,12 +1,14 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch
 configuration bench.py times.
 
-The CPU oracle cannot run these sizes in seconds, so each case checks
-  (1) sampled output blocks against the oracle, whose inputs are the raw seeded
-      tensors (copied block by block to the host), never anything the library wrote;
+Each case checks
+  (1) sampled output blocks against the oracle called one block at a time, whose
+      inputs are the raw seeded tensors (copied block by block to the host), never
+      anything the library wrote;
   (2) every output element against a separate evaluation with elementwise torch ops
       (IEEE fp32 multiply / add / round-half-even, one kernel per operation, so
       nothing is contracted) -- a property check that holds at any size.
+test_gpu_fullsize_oracle.py adds the whole-tensor comparison with the oracle.
 """
 import numpy as np
 import pytest
