@@ -462,3 +462,30 @@ def test_block_quotient_sequences_equal_division_for_every_mantissa(bits):
     at typical weight and gradient magnitudes, and at the binades next to qmax."""
     for exponent in (-100, -99, -24, -14, -10, -6, -1, 0, 1, 2, 3, 6, 7, 15, 64, 98, 99):
         assert zpp.selfcheck_block_scale(bits, exponent) == (0, 0), exponent
+
+
+@pytest.mark.parametrize("bits,block", [(4, 512), (4, 96), (8, 2048), (8, 160)])
+def test_decoders_accept_every_code_value(bits, block):
+    """Codes that no quantizer writes (nibble 0x8 = -8, byte 0x80 = -128) are still two's
+    complement to the decode and to both reduce stages: random bytes as codes."""
+    rng = np.random.default_rng(4242 + bits + block)
+    K, blocks = 5, 37
+    n = block * blocks
+    codes = [rng.integers(0, 256, size=n * bits // 8, dtype=np.uint8) for _ in range(K)]
+    for c in codes:
+        c[:16] = 0x88 if bits == 4 else 0x80                 # a run of the most negative code
+    scales = [(10.0 ** rng.uniform(-6, 2, size=blocks)).astype(np.float32) for _ in range(K)]
+    dcodes = [torch.from_numpy(c).to(DEV) for c in codes]
+    dscales = [torch.from_numpy(s).to(DEV) for s in scales]
+    for odt in (oracle.F32, oracle.F16, oracle.BF16):
+        y = torch.empty(n, dtype=TORCH_DT[odt], device=DEV)
+        zpp.qwz_dequantize(dcodes[0], dscales[0], n, block, bits, out=y)
+        torch.cuda.synchronize()
+        assert eq_bytes(y, oracle.qwz_dequantize(codes[0], scales[0], n, block, bits, odt))
+    hc, hs = oracle.qgz_intra_reduce(codes, scales, n, block, bits)
+    dc, ds = zpp.qgz_intra_reduce(dcodes, dscales, n, block, bits)
+    torch.cuda.synchronize()
+    assert eq_bytes(ds, hs) and eq_bytes(dc, hc)
+    out = zpp.qgz_inter_reduce(dcodes, dscales, n, block, bits, 3.0)
+    torch.cuda.synchronize()
+    assert eq_bytes(out, oracle.qgz_inter_reduce(codes, scales, n, block, bits, 3.0))

@@ -124,6 +124,35 @@ def test_int8_byte_layout_twos_complement():
     assert list(codes[:4]) == [0x7F, 0x81, 0xFF, 0x05]
 
 
+def test_every_code_value_decodes_as_twos_complement():
+    """The decoders accept any code, also the most negative one the quantizer never writes:
+    nibble 0x8 is -8 and byte 0x80 is -128 (two's complement), in the decode and in both
+    reduce stages."""
+    nib = np.arange(16)
+    codes4 = (nib | (((nib + 5) % 16) << 4)).astype(np.uint8)      # element 2i = i, element 2i+1 = (i+5) % 16
+    want4 = np.empty(32)
+    want4[0::2] = np.where(nib >= 8, nib - 16, nib)
+    hi = (nib + 5) % 16
+    want4[1::2] = np.where(hi >= 8, hi - 16, hi)
+    assert want4.min() == -8 and want4.max() == 7
+    scale = np.array([0.75], dtype=np.float32)
+    y = oracle.qwz_dequantize(codes4, scale, 32, 32, 4, F32)
+    assert np.array_equal(y, (want4 * 0.75).astype(np.float32))
+    out = oracle.qgz_inter_reduce([codes4, codes4], [scale, scale], 32, 32, 4, 2.0)
+    assert np.array_equal(out, (want4 * 0.75).astype(np.float32))
+    ic, isc = oracle.qgz_intra_reduce([codes4], [scale], 32, 32, 4)   # the sums -6 .. 5.25, absmax 6 = 8 * 0.75
+    assert isc[0] == np.float32(6.0) / np.float32(7.0)
+    assert ref64.unpack_nibbles(ic, 32)[list(want4).index(-8)] == -7
+
+    codes8 = np.arange(256, dtype=np.uint8)
+    want8 = codes8.view(np.int8).astype(np.float64)
+    assert want8.min() == -128
+    y = oracle.qwz_dequantize(codes8, scale, 256, 256, 8, F32)
+    assert np.array_equal(y, (want8 * 0.75).astype(np.float32))
+    out = oracle.qgz_inter_reduce([codes8], [scale], 256, 256, 8, 1.0)
+    assert np.array_equal(out, (want8 * 0.75).astype(np.float32))
+
+
 @pytest.mark.parametrize("bits", [8, 4])
 def test_ties_round_to_even(bits):
     """absmax = qmax*2^e makes inv = 2^-e exactly, so (k+1/2)*2^e lands exactly

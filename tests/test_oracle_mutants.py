@@ -37,9 +37,23 @@ MUTANTS = {
     "f16_ties_away": ("if (rest > 0x1000u || (rest == 0x1000u && (keep & 1u))) h += 1;",
                       "if (rest >= 0x1000u) h += 1;"),
     "f16_subnormal_scale_wrong": ("float v = (float)m * 0x1p-24f;", "float v = (float)m * 0x1p-25f;"),
+    "intra_sum_in_double": ("float s = 0.0f;\n            for (int k = 0; k < X; ++k)", "double s = 0.0;\n            for (int k = 0; k < X; ++k)"),
+    "inter_sum_in_double": ("float s = 0.0f;\n        for (int i = 0; i < Y; ++i)", "double s = 0.0;\n        for (int i = 0; i < Y; ++i)"),
+    "intra_decode_fused_into_the_add": (
+        "s = s + dequant_elem(codes_in[k], scales_in[k], bits, block, base + (size_t)i);",
+        "s = fmaf((float)get_code(codes_in[k], bits, base + (size_t)i), scales_in[k][(base + (size_t)i) / (size_t)block], s);"),
+    "inter_divides_every_addend": None,         # two edits, see below
+    "reorder_leaves_scales_unpermuted": ("scales[ob] = quant_block(v, block, bits, codes, out_base);",
+                                         "scales[in_base / (size_t)block] = quant_block(v, block, bits, codes, out_base);"),
+    "absmax_skips_last_element": ("for (int i = 0; i < B; ++i) {\n        float m = fabsf(v[i]);",
+                                  "for (int i = 0; i < B - 1; ++i) {\n        float m = fabsf(v[i]);"),
+    "nibble_eight_decoded_as_plus_eight": ("return nib >= 8 ? nib - 16 : nib;", "return nib > 8 ? nib - 16 : nib;"),
     "int8_code_sign_lost": ("if (bits == 8) return ((const int8_t*)codes)[i];", "if (bits == 8) return ((const uint8_t*)codes)[i];"),
 }
 TWO_EDITS = {
+    "inter_divides_every_addend": [("s = s + dequant_elem(codes_in[i], scales_in[i], bits, block, (size_t)e);",
+                                    "s = s + dequant_elem(codes_in[i], scales_in[i], bits, block, (size_t)e) / divisor;"),
+                                   ("out[e] = s / divisor;", "out[e] = s;")],
     "nibble_order_swapped_both_ways": [MUTANTS["high_nibble_first"],
                                        ("int nib = (i & 1) ? (b >> 4) : (b & 0xf);", "int nib = (i & 1) ? (b & 0xf) : (b >> 4);")],
 }
@@ -47,6 +61,13 @@ TWO_EDITS = {
 
 # the pin expected to catch each mistake (run first; every pin is tried if it does not)
 CAUGHT_BY = {
+             'intra_sum_in_double': 'tests/test_oracle_qgz.py::test_intra_reduce_matches_ordered_replay',
+             'inter_sum_in_double': 'tests/test_oracle_qgz.py::test_inter_reduce_matches_ordered_replay',
+             'intra_decode_fused_into_the_add': 'tests/test_oracle_qgz.py::test_intra_reduce_matches_ordered_replay',
+             'inter_divides_every_addend': 'tests/test_oracle_qgz.py::test_inter_reduce_matches_ordered_replay',
+             'reorder_leaves_scales_unpermuted': 'tests/test_oracle_qgz.py::test_fused_reorder_equals_quantize_then_permute',
+             'absmax_skips_last_element': 'tests/test_oracle_codec.py::test_every_finite_fp16_value_matches_second_evaluator',
+             'nibble_eight_decoded_as_plus_eight': 'tests/test_oracle_codec.py::test_every_code_value_decodes_as_twos_complement',
              'fused_reorder_reads_unpermuted': 'tests/test_oracle_qgz.py::test_fused_reorder_equals_quantize_then_permute',
              'reorder_roles_exchanged': 'tests/test_oracle_qgz.py::test_reorder_matches_the_papers_examples',
              'intra_sum_descending': 'tests/test_oracle_qgz.py::test_summation_order_is_ascending_peer_index',
@@ -86,7 +107,8 @@ def test_planted_mistake_is_caught(name, tmp_path):
         return subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *targets],
                               env=env, cwd=ROOT, capture_output=True, text=True)
 
-    r = pins(os.path.join(ROOT, *CAUGHT_BY[name].split("/")))
-    if r.returncode != 1:
+    first = CAUGHT_BY.get(name)
+    r = pins(os.path.join(ROOT, *first.split("/"))) if first else None
+    if r is None or r.returncode != 1:
         r = pins(os.path.join(ROOT, "tests", "test_oracle_qgz.py"), os.path.join(ROOT, "tests", "test_oracle_codec.py"))
     assert r.returncode == 1 and "failed" in r.stdout, f"mutant {name} survived every pin:\n{r.stdout[-2000:]}"
