@@ -48,6 +48,10 @@ MUTANTS = {
     "absmax_skips_last_element": ("for (int i = 0; i < B; ++i) {\n        float m = fabsf(v[i]);",
                                   "for (int i = 0; i < B - 1; ++i) {\n        float m = fabsf(v[i]);"),
     "nibble_eight_decoded_as_plus_eight": ("return nib >= 8 ? nib - 16 : nib;", "return nib > 8 ? nib - 16 : nib;"),
+    "f16_overflows_just_above_max": ("if (a >= 65520.0f) return", "if (a > 65504.0f) return"),
+    "f16_subnormal_narrowing_floors": ("float r = nearbyintf(a * 0x1p24f);", "float r = floorf(a * 0x1p24f);"),
+    "scatter_map_is_not_the_inverse": ("long long i = w / X, j = w % X;\n    return st * T + j * Y + i;",
+                                       "long long i = w / Y, j = w % Y;\n    return st * T + j * Y + i;"),
     "int8_code_sign_lost": ("if (bits == 8) return ((const int8_t*)codes)[i];", "if (bits == 8) return ((const uint8_t*)codes)[i];"),
 }
 TWO_EDITS = {
