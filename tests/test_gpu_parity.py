@@ -215,6 +215,8 @@ REORDER_CASES = [
     (1, 7, 1, 256, 4, 5),
     (16, 1, 2, 128, 8, 3),
     (8, 6, 1, 512, 4, 2731),       # 8193+ workgroups: the XCD remap is active, tiles end ragged in every slice
+    (4, 6, 3, 512, 4, 2049),       # the same with three pipeline stages
+    (2, 3, 2, 2048, 8, 1501),      # and for int8 blocks of 2048 with two stages
 ]
 
 
