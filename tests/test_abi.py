@@ -69,6 +69,27 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.qwz_quantize(None, 0, 0, 32, 8, None, None, None) == 0
 
 
+def test_sizes_beyond_the_launch_limits_are_rejected_on_the_host():
+    """Tensors whose grid would not fit a launch (2^31 - 1 workgroups, 2^32 wave tiles) come back
+    as ZPP_EINVAL.  Only where no GPU is present: the pointers are fake, and a regression of
+    these checks must not be able to launch on them."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("host-only check, run where there is no GPU")
+    L = zpp.lib()
+    fake = ctypes.c_void_p(0x1000)
+    table = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    huge = 1 << 50
+    assert L.qwz_quantize(fake, 0, huge, 2048, 8, fake, fake, None) == -1
+    assert L.qwz_quantize(fake, 0, 96 << 40, 96, 4, fake, fake, None) == -1      # generic block path
+    assert L.qwz_dequantize(fake, fake, huge, 2048, 8, 1, fake, None) == -1
+    assert L.qgz_reorder(fake, 0, huge, 8, 48, 1, 512, 4, fake, fake, None) == -1
+    assert L.qgz_intra_reduce(table, table, 2, huge, 512, 4, fake, fake, None) == -1
+    assert L.qgz_intra_reduce(table, table, 2, 96 << 40, 96, 4, fake, fake, None) == -1
+    assert L.qgz_inter_reduce(table, table, 2, huge, 512, 4, ctypes.c_float(2.0), fake, None) == -1
+    assert L.zpp_stream_copy(fake, fake, 1 << 60, None) == -1
+
+
 def test_reorder_helpers_equal_oracle_on_many_shapes():
     """The host helpers share the kernels' index arithmetic (divisions by launch constants
     done with a multiply-high); compare with the oracle's plain divisions."""
