@@ -1,6 +1,8 @@
 """Seeded random sweep over the valid argument space of the five operations: dtypes, code
 widths, block sizes (powers of two and not), X, Y, S, divisors and value ranges that no
 hand-picked case combines.  Every output byte is compared with the oracle."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -45,7 +47,8 @@ def draw_values(rng, n, block, dtype):
     return t
 
 
-@pytest.mark.parametrize("seed", range(160))
+# ZPP_SWEEP_SEEDS widens the sweep for an occasional long run
+@pytest.mark.parametrize("seed", range(int(os.environ.get("ZPP_SWEEP_SEEDS", "160"))))
 def test_random_configuration(seed):
     rng = np.random.default_rng(9000 + seed)
     dtype = [oracle.F16, oracle.BF16, oracle.F32][int(rng.integers(0, 3))]
