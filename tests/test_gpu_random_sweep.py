@@ -56,6 +56,8 @@ def test_random_configuration(seed):
     block = int(rng.choice(BLOCKS))
     X, Y, S = int(rng.integers(1, 10)), int(rng.integers(1, 10)), int(rng.integers(1, 4))
     bps = int(rng.integers(1, 5))
+    if seed % 16 == 0:                                   # every 16th draw is large: grids beyond the XCD-remap threshold
+        bps *= max(1, (24 << 20) // (S * X * Y * block * bps))
     L = block * bps                                      # elements per slice
     n = S * X * Y * L
     print(f"seed={seed} dtype={dtype} bits={bits} block={block} X={X} Y={Y} S={S} bps={bps} n={n}", flush=True)
