@@ -34,6 +34,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef ZPP_DEQ_V
 #define ZPP_DEQ_V 2
 #endif
+// dequantize: one scalar fetch of the scale per wave when its tile lies inside one block
+#ifndef ZPP_DEQ_ONE_BLOCK
+#define ZPP_DEQ_ONE_BLOCK 1
+#endif
 // quantize: loads a wave keeps in flight (0 = all of the tile's).  One measured best: with
 // eight waves per SIMD that already covers the bandwidth-delay product, and more bytes
 // in flight only queue up in the memory system (-7 % with all four loads outstanding).
@@ -526,7 +530,9 @@ __device__ __forceinline__ float byte_f32(uint32_t w, int i)
 // One tile of qwz_dequantize.  Lanes past the end of the tensor are masked; the masked
 // form is kept for full tiles too: it issues each 16-byte store as soon as its eight
 // values are ready, which measured 2 % faster than an unmasked variant that stored last.
-template <int ODT, int BITS, int V, bool POW2>
+// ONE_BLOCK: the block is a multiple of the tile, so the whole wave shares one scale, which is
+// then fetched once through the scalar unit instead of once per lane and step.
+template <int ODT, int BITS, int V, bool POW2, bool ONE_BLOCK>
 __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ codes, const float* __restrict__ scales,
                                                 void* __restrict__ y, uint64_t base, uint64_t rem, uint32_t B,
                                                 int log2b, int lane)
@@ -534,6 +540,8 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ code
     uint32_t w[V][2];
     float s[V];
     bool ok[V];
+    float s_tile = 0.0f;
+    if constexpr (ONE_BLOCK) s_tile = scales[base >> log2b];  // base is the same in every lane
 #pragma unroll
     for (int k = 0; k < V; ++k) {
         const uint32_t off = (uint32_t)(k * kWave + lane) * 8u;
@@ -549,8 +557,12 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ code
             } else {
                 w[k][0] = ld_stream(reinterpret_cast<const uint32_t*>(codes + (e >> 1)));
             }
-            const uint64_t blk = POW2 ? (e >> log2b) : (e / B);
-            s[k] = scales[blk];
+            if constexpr (ONE_BLOCK) {
+                s[k] = s_tile;
+            } else {
+                const uint64_t blk = POW2 ? (e >> log2b) : (e / B);
+                s[k] = scales[blk];
+            }
         }
     }
 #pragma unroll
@@ -584,7 +596,7 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ code
     }
 }
 
-template <int ODT, int BITS, int V, bool POW2>
+template <int ODT, int BITS, int V, bool POW2, bool ONE_BLOCK>
 __global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restrict__ codes,
                                                          const float* __restrict__ scales,
                                                          void* __restrict__ y, uint64_t n, uint32_t B,
@@ -595,7 +607,7 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restri
     const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t base = wid * TILE;
     if (base >= n) return;
-    dequantize_tile<ODT, BITS, V, POW2>(codes, scales, y, base, n - base, B, log2b, lane);
+    dequantize_tile<ODT, BITS, V, POW2, ONE_BLOCK>(codes, scales, y, base, n - base, B, log2b, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -1128,12 +1140,15 @@ int qwz_dequantize(const void* codes, const float* scales, size_t n, int block, 
     const uint8_t* c = static_cast<const uint8_t*>(codes);
     const int l2 = log2_or_neg((uint32_t)block);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool one_block = ZPP_DEQ_ONE_BLOCK && block % (512 * V) == 0;  // a wave's tile inside one block
 #define ZPP_D(ODT, BITS)                                                                                          \
     do {                                                                                                          \
-        if (l2 >= 0)                                                                                              \
-            k_dequantize<ODT, BITS, V, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift);  \
+        if (l2 >= 0 && one_block)                                                                                 \
+            k_dequantize<ODT, BITS, V, true, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift);  \
+        else if (l2 >= 0)                                                                                         \
+            k_dequantize<ODT, BITS, V, true, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift);  \
         else                                                                                                      \
-            k_dequantize<ODT, BITS, V, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift); \
+            k_dequantize<ODT, BITS, V, false, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(c, scales, y, n, (uint32_t)block, l2, xcd_shift); \
     } while (0)
     if (bits == 8) {
         if (out_dtype == ZPP_F16) ZPP_D(ZPP_F16, 8);
