@@ -75,7 +75,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2306_10209_amd import binding as zpp, workloads
+    from paper_2306_10209_amd import binding as zpp, diagnostics, workloads
 
     zpp.lib()  # fail loudly if the HIP library is missing
     if not torch.cuda.is_available():
@@ -219,12 +219,12 @@ def main():
     src = grad.view(torch.uint8)[: 1 << 31]
     dst = wout.view(torch.uint8)[: 1 << 31]
     for _ in range(2):
-        zpp.stream_copy(dst, src)
+        diagnostics.stream_copy(dst, src)
     ce = []
     for _ in range(5):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        zpp.stream_copy(dst, src)
+        diagnostics.stream_copy(dst, src)
         b.record()
         ce.append((a, b))
     torch.cuda.synchronize()
@@ -333,7 +333,7 @@ def per_config_kernels(torch, zpp, workloads, dev):
             fn()
         ev = []
         for _ in range(rounds):
-            zpp.stream_copy(blk_dst, blk_src)
+            diagnostics.stream_copy(blk_dst, blk_src)
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             for _ in range(batch):

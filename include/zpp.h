@@ -56,7 +56,6 @@ extern "C" {
 #define ZPP_OK 0
 #define ZPP_EINVAL (-1)       /* bad argument: null, misaligned, size not a multiple, out of range */
 #define ZPP_ELAUNCH (-2)      /* the HIP runtime reported an error for the launch */
-#define ZPP_EUNSUPPORTED (-3) /* valid per the paper's problem statement but not built here */
 
 #define ZPP_F16 0
 #define ZPP_BF16 1
@@ -136,25 +135,6 @@ int qgz_intra_reduce(const void* const* codes_in, const float* const* scales_in,
 int qgz_inter_reduce(const void* const* codes_in, const float* const* scales_in, int nodes,
                      size_t m, int block, int bits, float divisor,
                      float* out, void* stream);
-
-/*
- * zpp_selfcheck_block_scale - diagnostic.  The encoders take a block's two quotients
- * (absmax/qmax and qmax/absmax, Sec. 3.1's per-block scaling coefficient and its
- * inverse) by short fused multiply-add sequences instead of division instructions.
- * This call checks, on the device it runs on, that the sequences give the correctly
- * rounded quotients: for every one of the 2^23 fp32 mantissas at binary exponent
- * `exponent` (-100 .. 99) it compares them with plain division and ADDS the number
- * of differing a/qmax results to counts[0] and of qmax/a results to counts[1]
- * (device memory, 8-byte aligned, zeroed by the caller).  Both stay 0.
- */
-int zpp_selfcheck_block_scale(int bits, int exponent, unsigned long long* counts, void* stream);
-
-/*
- * zpp_stream_copy - measurement helper, not part of the paper's method: copies
- * `bytes` (a multiple of 16) from src to dst, 16 bytes per lane, as the bandwidth
- * ceiling the kernels are compared with (Sec. 4.2 claims full memory bandwidth).
- */
-int zpp_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -1,5 +1,4 @@
-"""Compile the HIP kernels + C ABI into paper_2306_10209_amd/lib/libzpp_gfx950.so, and the
-stand-alone streaming-bandwidth probe into paper_2306_10209_amd/lib/stream_probe.
+"""Compile the HIP kernels + C ABI into paper_2306_10209_amd/lib/libzpp_gfx950.so.
 
 gfx950 only.  -ffp-contract=off keeps every fp32 operation separately rounded
 (the bit-exactness contract of include/zpp.h); packed-fp32 instruction selection
@@ -24,7 +23,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-fn
 
 def build(force: bool = True, extra=()) -> str:
     os.makedirs(LIBDIR, exist_ok=True)
-    deps = [SRC, os.path.join(INC, "zpp.h")]
+    deps = [SRC, os.path.join(INC, "zpp.h"), os.path.join(INC, "zpp_diagnostics.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     cmd = [HIPCC, *FLAGS, *extra, SRC, "-o", LIB]
@@ -32,21 +31,5 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
-PROBE_SRC = os.path.join(PKG, "csrc", "stream_probe.hip")
-PROBE = os.path.join(LIBDIR, "stream_probe")
-
-
-def build_probe(force: bool = True) -> str:
-    """The measurement tool behind profiles/streaming_ceilings.txt (an executable, not part of the library)."""
-    os.makedirs(LIBDIR, exist_ok=True)
-    if not force and os.path.exists(PROBE) and os.path.getmtime(PROBE) >= os.path.getmtime(PROBE_SRC):
-        return PROBE
-    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", PROBE_SRC, "-o", PROBE]
-    subprocess.run(cmd, check=True)
-    return PROBE
-
-
 if __name__ == "__main__":
     print(build(force=True, extra=sys.argv[1:]))
-    print(build_probe(force=True))

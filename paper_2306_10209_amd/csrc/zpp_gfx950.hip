@@ -12,8 +12,10 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "zpp.h"
+#include "zpp_diagnostics.h"
 
 namespace {
 
@@ -21,91 +23,40 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Tuning constants (all measured on MI355X; -D overrides are for experiments).
+// Tile shapes (all measured on MI355X).
 //
 // Loads per lane and tile, i.e. a wave's tile is 512 * V elements.  Best: two for int8
 // output and for dequantize, four for int4 output, whose stores are narrower.
-#ifndef ZPP_QUANT_V8
-#define ZPP_QUANT_V8 2
-#endif
-#ifndef ZPP_QUANT_V4
-#define ZPP_QUANT_V4 4
-#endif
-#ifndef ZPP_DEQ_V
-#define ZPP_DEQ_V 2
-#endif
-// dequantize: one scalar fetch of the scale per wave when its tile lies inside one block
-#ifndef ZPP_DEQ_ONE_BLOCK
-#define ZPP_DEQ_ONE_BLOCK 1
-#endif
-// quantize: loads a wave keeps in flight (0 = all of the tile's).  One measured best: with
-// eight waves per SIMD that already covers the bandwidth-delay product, and more bytes
-// in flight only queue up in the memory system (-7 % with all four loads outstanding).
-#ifndef ZPP_QUANT_INFLIGHT
-#define ZPP_QUANT_INFLIGHT 1
-#endif
-// reduce stages: peers fetched per group, and whether the next group is fetched ahead
-#ifndef ZPP_RED_U
-#define ZPP_RED_U 4
-#endif
-#ifndef ZPP_RED_PREFETCH
-#define ZPP_RED_PREFETCH true
-#endif
-// qgz_intra_reduce: preferred code dwords a lane takes per peer (1, 2 or 4)
-#ifndef ZPP_INTRA_NW
-#define ZPP_INTRA_NW 4
-#endif
-// qgz_inter_reduce: code dwords a lane takes per peer (1, 2 or 4)
-#ifndef ZPP_INTER_NW
-#define ZPP_INTER_NW 1
-#endif
+constexpr int kQuantV8 = 2;
+constexpr int kQuantV4 = 4;
+constexpr int kDeqV = 2;
 
 constexpr int kWave = 64;
-#ifndef ZPP_WAVES_PER_WG
-#define ZPP_WAVES_PER_WG 4
-#endif
-constexpr int kWavesPerWG = ZPP_WAVES_PER_WG;
+constexpr int kWavesPerWG = 4;
 constexpr int kThreads = kWave * kWavesPerWG;
 constexpr float kTiny = 0x1p-100f;  // blocks with a smaller maximum are coded as all zero
 
 // Streaming accesses: every byte is touched once, so loads and stores carry the
 // non-temporal hint (measured: +5 % on loads, +2 % on stores against plain accesses;
 // wider-scope write-through store policies gave nothing further in these kernels).
-// ZPP_NT_LOAD / ZPP_NT_STORE = 0 switch the hint off for experiments.
-#ifndef ZPP_NT_LOAD
-#define ZPP_NT_LOAD 1
-#endif
-#ifndef ZPP_NT_STORE
-#define ZPP_NT_STORE 1
-#endif
 template <class T>
 __device__ __forceinline__ T ld_stream(const T* p)
 {
-#if ZPP_NT_LOAD
     return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
 }
 template <class T>
 __device__ __forceinline__ void st_stream(T v, T* p)
 {
-#if ZPP_NT_STORE
     __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
 }
 
 // Workgroups are handed to the 8 XCDs round-robin by their index.  For large grids
 // the quantize and dequantize kernels remap the index so that each XCD works through
-// runs of 2^ZPP_XCD_SHIFT consecutive tiles (measured 2-4 % faster than interleaving
+// runs of 2^kXcdShift consecutive tiles (measured 2-4 % faster than interleaving
 // single tiles over the XCDs).  The grid is then padded to a multiple of 8 runs and
 // surplus groups exit at once; small grids keep the plain order (shift < 0).
-#ifndef ZPP_XCD_SHIFT
-#define ZPP_XCD_SHIFT 6
-#endif
-constexpr uint64_t kXcdMinGrid = 16ull * 8ull << (ZPP_XCD_SHIFT > 0 ? ZPP_XCD_SHIFT : 0);
+constexpr int kXcdShift = 6;
+constexpr uint64_t kXcdMinGrid = 16ull * 8ull << kXcdShift;
 
 __device__ __forceinline__ uint64_t logical_block(int xcd_shift)
 {
@@ -119,9 +70,9 @@ __device__ __forceinline__ uint64_t logical_block(int xcd_shift)
 inline uint64_t plan_grid(uint64_t groups, int& xcd_shift)
 {
     xcd_shift = -1;
-    if (ZPP_XCD_SHIFT < 0 || groups < kXcdMinGrid) return groups;
-    xcd_shift = ZPP_XCD_SHIFT;
-    const uint64_t q = 8ull << ZPP_XCD_SHIFT;
+    if (groups < kXcdMinGrid) return groups;
+    xcd_shift = kXcdShift;
+    const uint64_t q = 8ull << kXcdShift;
     return (groups + q - 1) / q * q;
 }
 
@@ -387,10 +338,13 @@ __device__ __host__ __forceinline__ uint64_t source_slice32(uint32_t p, uint32_t
 // maximum and the encode (Sec. 4.2), so the tensor is read exactly once.
 
 // One tile.  FULL: the whole tile lies inside the slice, so no lane is masked;
-// otherwise lanes past the end of the slice are masked.  A wave waits for each load
-// before it issues the next (ZPP_QUANT_INFLIGHT): the other waves of the SIMD keep
-// the memory system busy.
-template <int DT, int BITS, int LOG2B, int V, bool FULL>
+// otherwise lanes past the end of the slice are masked.  DEEP = false: a wave waits
+// for each load before it issues the next; with a grid of many residency rounds the
+// other waves of the SIMD keep the memory system busy, and more bytes in flight only
+// queue up (-7 % with all of a tile's loads outstanding).  DEEP = true: all of the
+// tile's loads are issued at once; for a launch of one or two rounds the chip is not
+// yet (or no longer) full, and a wave's own latency chain is what the launch lasts.
+template <int DT, int BITS, int LOG2B, int V, bool FULL, bool DEEP>
 __device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                               float* __restrict__ scales, uint64_t in_base, uint64_t out_base,
                                               uint64_t rem, int lane)
@@ -408,9 +362,7 @@ __device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_
 #pragma unroll
             for (int i = 0; i < 8; ++i) f[k][i] = 0.0f;
         }
-#if ZPP_QUANT_INFLIGHT > 0
-        if ((k + 1) % ZPP_QUANT_INFLIGHT == 0) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-#endif
+        if (!DEEP) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     }
 
     if constexpr (B >= 512) {
@@ -447,7 +399,7 @@ __device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_
     }
 }
 
-template <int DT, int BITS, int LOG2B, int V>
+template <int DT, int BITS, int LOG2B, int V, bool DEEP>
 __global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                                        float* __restrict__ scales, uint64_t L,
                                                        FastDiv by_tiles_per_slice, uint32_t total_tiles,
@@ -464,9 +416,9 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ 
     const uint64_t out_base = (uint64_t)p * L + (uint64_t)t * TILE;
     const uint64_t rem = L - (uint64_t)t * TILE;  // elements of this slice from the tile start on (>= 1)
     if (rem >= TILE)
-        quantize_tile<DT, BITS, LOG2B, V, true>(x, codes, scales, in_base, out_base, rem, lane);
+        quantize_tile<DT, BITS, LOG2B, V, true, DEEP>(x, codes, scales, in_base, out_base, rem, lane);
     else
-        quantize_tile<DT, BITS, LOG2B, V, false>(x, codes, scales, in_base, out_base, rem, lane);
+        quantize_tile<DT, BITS, LOG2B, V, false, DEEP>(x, codes, scales, in_base, out_base, rem, lane);
 }
 
 // Any block size that is a multiple of 32 (not a power of two, or larger than the
@@ -620,7 +572,7 @@ struct PeerTable {
 };
 
 // elements a lane holds per vector of NW code dwords (NW = 1, 2 or 4)
-template <int BITS, int NW = 4>
+template <int BITS, int NW>
 struct EPL {
     static constexpr int value = NW * 32 / BITS;
 };
@@ -641,66 +593,85 @@ __device__ __forceinline__ void load_words(const uint8_t* __restrict__ p, uint32
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-// acc[0..8) += decode(nibble_i of w, s), i = 0..7 (nibble i = bits 4i..4i+3).
+// The three operands of the exact int4 decode for a scale s with |s| < 2^100:
+// s * 2^24, s * 2^20 and -8 * s (power-of-two factors, so all three are exact).
+struct Dec4 {
+    float lo, hi, bias;
+};
+__device__ __forceinline__ Dec4 dec4_operands(float s)
+{
+    Dec4 d;
+    d.lo = s * 0x1p24f;
+    d.hi = s * 0x1p20f;
+    d.bias = s * -8.0f;
+    return d;
+}
+__device__ __forceinline__ bool dec4_exact(float s) { return fabsf(s) < 0x1p100f; }
+
+// acc[0..8) (+)= decode(nibble_i of w, s), i = 0..7 (nibble i = bits 4i..4i+3).
 //
 // decode is float(q)*s with one rounding.  It is computed as a single fused
 // multiply-add whose multiplicand is read straight from the code word: after
 // flipping each nibble's top bit the nibble holds u = q + 8, and a 16-bit lane
 // whose only set bits are such a nibble is, read as binary16, the subnormal
 // u*2^-24 (bits 0-3) or u*2^-20 (bits 4-7).  fma(u*2^-24, s*2^24, -8*s) is the
-// exact value (u-8)*s = q*s rounded once, because s*2^24, s*2^20 and 8*s are exact
-// (power-of-two factors, s < 2^100 checked by the caller).  The conversion of the
-// binary16 operand happens inside the mixed-precision fma instruction.
+// exact value (u-8)*s = q*s rounded once, because s*2^24, s*2^20 and 8*s are exact.
+// The conversion of the binary16 operand happens inside the mixed-precision fma
+// instruction.
 //
-// FIRST: the accumulator is set instead of added to.  The sum starts from +0 and a decoded
-// value is never -0 (code 0 gives 8s - 8s = +0, a zero scale gives +0 + -0 = +0), so
-// 0 + d and d are the same bits and the first peer needs neither the zeroing nor the add.
+// FIRST: the accumulator is set instead of added to.  The sum starts from +0 and a value
+// decoded this way is never -0 (code 0 gives 8s - 8s = +0 for either sign of s, a zero scale
+// of either sign gives a sum of two opposite zeros = +0), so 0 + d and d are the same bits
+// and the first peer needs neither the zeroing nor the add.
 template <bool FIRST>
-__device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w, float s_lo, float s_hi,
-                                             float bias)
+__device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w, const Dec4& d)
 {
     // (x ^ 0x88888888) & mask in one three-input bit operation each
     const uint32_t v = w >> 8;
     const f16x2 a = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(w, 0x88888888u, 0x000F000Fu, 0x28));  // elements 0, 4
     const f16x2 b = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(w, 0x88888888u, 0x00F000F0u, 0x28));  // elements 1, 5
     const f16x2 c = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(v, 0x88888888u, 0x000F000Fu, 0x28));  // elements 2, 6
-    const f16x2 d = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(v, 0x88888888u, 0x00F000F0u, 0x28));  // elements 3, 7
-    acc[0] = FIRST ? __builtin_fmaf((float)a.x, s_lo, bias) : acc[0] + __builtin_fmaf((float)a.x, s_lo, bias);
-    acc[1] = FIRST ? __builtin_fmaf((float)b.x, s_hi, bias) : acc[1] + __builtin_fmaf((float)b.x, s_hi, bias);
-    acc[2] = FIRST ? __builtin_fmaf((float)c.x, s_lo, bias) : acc[2] + __builtin_fmaf((float)c.x, s_lo, bias);
-    acc[3] = FIRST ? __builtin_fmaf((float)d.x, s_hi, bias) : acc[3] + __builtin_fmaf((float)d.x, s_hi, bias);
-    acc[4] = FIRST ? __builtin_fmaf((float)a.y, s_lo, bias) : acc[4] + __builtin_fmaf((float)a.y, s_lo, bias);
-    acc[5] = FIRST ? __builtin_fmaf((float)b.y, s_hi, bias) : acc[5] + __builtin_fmaf((float)b.y, s_hi, bias);
-    acc[6] = FIRST ? __builtin_fmaf((float)c.y, s_lo, bias) : acc[6] + __builtin_fmaf((float)c.y, s_lo, bias);
-    acc[7] = FIRST ? __builtin_fmaf((float)d.y, s_hi, bias) : acc[7] + __builtin_fmaf((float)d.y, s_hi, bias);
+    const f16x2 e = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(v, 0x88888888u, 0x00F000F0u, 0x28));  // elements 3, 7
+    acc[0] = FIRST ? __builtin_fmaf((float)a.x, d.lo, d.bias) : acc[0] + __builtin_fmaf((float)a.x, d.lo, d.bias);
+    acc[1] = FIRST ? __builtin_fmaf((float)b.x, d.hi, d.bias) : acc[1] + __builtin_fmaf((float)b.x, d.hi, d.bias);
+    acc[2] = FIRST ? __builtin_fmaf((float)c.x, d.lo, d.bias) : acc[2] + __builtin_fmaf((float)c.x, d.lo, d.bias);
+    acc[3] = FIRST ? __builtin_fmaf((float)e.x, d.hi, d.bias) : acc[3] + __builtin_fmaf((float)e.x, d.hi, d.bias);
+    acc[4] = FIRST ? __builtin_fmaf((float)a.y, d.lo, d.bias) : acc[4] + __builtin_fmaf((float)a.y, d.lo, d.bias);
+    acc[5] = FIRST ? __builtin_fmaf((float)b.y, d.hi, d.bias) : acc[5] + __builtin_fmaf((float)b.y, d.hi, d.bias);
+    acc[6] = FIRST ? __builtin_fmaf((float)c.y, d.lo, d.bias) : acc[6] + __builtin_fmaf((float)c.y, d.lo, d.bias);
+    acc[7] = FIRST ? __builtin_fmaf((float)e.y, d.hi, d.bias) : acc[7] + __builtin_fmaf((float)e.y, d.hi, d.bias);
 }
 
-// acc[i] += decode(code_i, s) for the codes of NW dwords, in place
+// acc[i] (+)= float(code_i) * s for the codes of NW dwords by convert and multiply (any
+// scale).  The product can be -0 (code 0 and a negative scale, a negative code and a zero
+// scale), so the first peer is added to the +0 the sum starts from.
+template <int BITS, int NW, bool FIRST>
+__device__ __forceinline__ void accumulate_plain(float (&acc)[(EPL<BITS, NW>::value)], const uint32_t (&d)[NW], float s)
+{
+    constexpr int F = 32 / BITS;
+#pragma unroll
+    for (int j = 0; j < NW; ++j)
+#pragma unroll
+        for (int i = 0; i < F; ++i) {
+            const float v = (BITS == 4 ? nibble_f32(d[j], i) : byte_f32(d[j], i)) * s;
+            acc[j * F + i] = FIRST ? 0.0f + v : acc[j * F + i] + v;
+        }
+}
+
+// ---------------------------------------------------------------------------
+// reduce stages, any block size: every lane fetches its own scales
+// ---------------------------------------------------------------------------
+
+// acc[i] (+)= decode(code_i, s) for the codes of NW dwords
 template <int BITS, int NW, bool FIRST>
 __device__ __forceinline__ void accumulate(float (&acc)[(EPL<BITS, NW>::value)], const uint32_t (&d)[NW], float s)
 {
-    if (BITS == 4) {
-        if (s < 0x1p100f) {
-            const float s_lo = s * 0x1p24f, s_hi = s * 0x1p20f, bias = s * -8.0f;
+    if (BITS == 4 && dec4_exact(s)) {
+        const Dec4 op = dec4_operands(s);
 #pragma unroll
-            for (int j = 0; j < NW; ++j) add_nibbles8<FIRST>(acc + j * 8, d[j], s_lo, s_hi, bias);
-        } else {  // scales this large never come from 16-bit gradients; plain convert and multiply
-#pragma unroll
-            for (int j = 0; j < NW; ++j)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float v = nibble_f32(d[j], i) * s;  // int -> float never gives -0
-                    acc[j * 8 + i] = FIRST ? v : acc[j * 8 + i] + v;
-                }
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < NW; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float v = byte_f32(d[j], i) * s;
-                acc[j * 4 + i] = FIRST ? v : acc[j * 4 + i] + v;
-            }
+        for (int j = 0; j < NW; ++j) add_nibbles8<FIRST>(acc + j * 8, d[j], op);
+    } else {  // int8, and int4 scales so large that they never come from 16-bit gradients
+        accumulate_plain<BITS, NW, FIRST>(acc, d, s);
     }
 }
 
@@ -725,10 +696,11 @@ __device__ __forceinline__ void add_group(float (&acc)[(EPL<BITS, NW>::value)], 
     for (int u = 1; u < U; ++u) accumulate<BITS, NW, false>(acc, w[u], s[u]);
 }
 
-// Sum of the K >= 1 peers' decoded values for the EPL elements starting at element e.
-// Peers are added in ascending order.  They are fetched in groups of U; with
-// PREFETCH the next group's loads are issued before the current group is decoded.
-template <int BITS, int NW, int U, bool PREFETCH>
+// Sum of the K >= 1 peers' decoded values for the EPL elements starting at element e,
+// whose scales are entry blk of the peers' scale arrays.  Peers are added in ascending
+// order.  They are fetched in groups of U, the next group's loads issued before the
+// current group is decoded.
+template <int BITS, int NW, int U>
 __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t e, uint64_t blk,
                                              float (&acc)[(EPL<BITS, NW>::value)])
 {
@@ -739,16 +711,14 @@ __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t
         uint32_t wa[U][NW], wb[U][NW];
         float sa[U], sb[U];
         load_group<NW, U>(P, 0, byte_off, blk, wa, sa);
-        if (PREFETCH && full > 1) load_group<NW, U>(P, U, byte_off, blk, wb, sb);
+        if (full > 1) load_group<NW, U>(P, U, byte_off, blk, wb, sb);
         add_group<BITS, NW, U, true>(acc, wa, sa);
         // groups 1 .. full-1, alternating between the two register sets
         for (int g = 1; g < full; g += 2) {
-            if (!PREFETCH) load_group<NW, U>(P, g * U, byte_off, blk, wb, sb);
-            if (PREFETCH && g + 1 < full) load_group<NW, U>(P, (g + 1) * U, byte_off, blk, wa, sa);
+            if (g + 1 < full) load_group<NW, U>(P, (g + 1) * U, byte_off, blk, wa, sa);
             add_group<BITS, NW, U, false>(acc, wb, sb);
             if (g + 1 < full) {
-                if (!PREFETCH) load_group<NW, U>(P, (g + 1) * U, byte_off, blk, wa, sa);
-                if (PREFETCH && g + 2 < full) load_group<NW, U>(P, (g + 2) * U, byte_off, blk, wb, sb);
+                if (g + 2 < full) load_group<NW, U>(P, (g + 2) * U, byte_off, blk, wb, sb);
                 add_group<BITS, NW, U, false>(acc, wa, sa);
             }
         }
@@ -768,6 +738,264 @@ __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t
     }
 }
 
+// The same sum with one peer at a time and convert-and-multiply decodes: the path of the
+// row-form kernels for scales their exact int4 decode cannot take.
+template <int BITS, int NW>
+__device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, uint64_t e, uint64_t blk,
+                                                   float (&acc)[(EPL<BITS, NW>::value)])
+{
+    const uint64_t byte_off = e * BITS / 8;
+    uint32_t w[NW];
+    load_words<NW>(P.codes[0] + byte_off, w);
+    accumulate_plain<BITS, NW, true>(acc, w, P.scales[0][blk]);
+    for (int k = 1; k < K; ++k) {
+        load_words<NW>(P.codes[k] + byte_off, w);
+        accumulate_plain<BITS, NW, false>(acc, w, P.scales[k][blk]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// reduce stages, row form: power-of-two blocks of at least 16 lanes x E elements
+// ---------------------------------------------------------------------------
+//
+// A lane takes, per peer, C vectors of NW code dwords (E = NW * 32 / BITS elements each);
+// vector c of lane l starts at element (c * 64 + l) * E of the wave's tile, so every
+// wave-wide load is one contiguous run.  When 16 * E divides the block, the 16 lanes of a
+// row (lanes 16r .. 16r+15) decode with one scale per peer, and the scales travel through
+// LDS instead of through per-lane loads: before the first peer, lane j of each row fetches
+// the scales of peers j, j+16, j+32, j+48 for the row's block (a few wave-wide loads cover
+// all peers), derives the operands of the int4 decode for them and parks them in a table
+// of the wave; each peer's operands are then read back with one broadcast LDS read per
+// row.  That takes the scale load, its address arithmetic and the three multiplies per
+// peer and lane off the vector ALU, which is what bounds these kernels.
+//
+// Codes are fetched in groups of U peers into two register sets, the next group's loads
+// issued before the current group is decoded; every branch of the steady state leaves
+// the loop, so the wait before a decode never includes the loads issued after it.
+
+// One wave's table: [vector c][row r][peer k][operand], PL operands per peer (int4: s * 2^24,
+// s * 2^20, -8 s; int8: s).  The row pitch is odd, so the 4 rows, which are read together,
+// fall into different banks.
+template <int BITS, int C>
+struct RowTable {
+    static constexpr int PL = BITS == 4 ? 3 : 1;
+    static constexpr int row_pitch = (ZPP_MAX_PEERS * PL) | 1;
+    static constexpr int floats = C * 4 * row_pitch;
+};
+
+// The wave's table is filled in three steps, so that the two dependent fetches it needs can be
+// issued early and waited for late.  The host repeats the last peer in the unused entries of
+// the pointer table, so all ZPP_MAX_PEERS entries can be read.
+constexpr int kRowChunks = ZPP_MAX_PEERS / 16;
+
+// 1: lane j of every row takes the scale pointers of peers j, j + 16, j + 32, j + 48
+__device__ __forceinline__ void row_scale_pointers(const PeerTable& P, int lane, const float* (&sp)[kRowChunks])
+{
+#pragma unroll
+    for (int i = 0; i < kRowChunks; ++i) sp[i] = P.scales[i * 16 + (lane & 15)];
+}
+
+// 2: their scales for the block of the lane's row in each vector (blk[c]: equal in the 16 lanes of a row)
+template <int C>
+__device__ __forceinline__ void row_scale_loads(const float* const (&sp)[kRowChunks], const uint64_t (&blk)[C],
+                                                float (&s)[kRowChunks][C])
+{
+#pragma unroll
+    for (int i = 0; i < kRowChunks; ++i)
+#pragma unroll
+        for (int c = 0; c < C; ++c) s[i][c] = sp[i][blk[c]];
+}
+
+// What a wave learns about its scales while it writes its table.
+struct RowScaleFacts {
+    bool exact;  // every int4 scale can take the exact decode (else the table must not be used)
+    bool mid;    // every scale is 0 or 2^-30 <= |s| < 2^60: nonzero sums then lie in [2^-53, 2^69)
+};
+
+// 3: the decode operands go to the table
+template <int BITS, int C>
+__device__ __forceinline__ RowScaleFacts write_row_table(const float (&s)[kRowChunks][C], int lane,
+                                                         float* __restrict__ tab)
+{
+    using T = RowTable<BITS, C>;
+    const int j = lane & 15, row = lane >> 4;
+    bool fine = true, mid = true;
+#pragma unroll
+    for (int i = 0; i < kRowChunks; ++i)
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            float* t = tab + (c * 4 + row) * T::row_pitch + (i * 16 + j) * T::PL;
+            const float mag = fabsf(s[i][c]);
+            mid = mid && (mag == 0.0f || (mag >= 0x1p-30f && mag < 0x1p60f));
+            if (BITS == 4) {
+                const Dec4 op = dec4_operands(s[i][c]);
+                fine = fine && dec4_exact(s[i][c]);
+                t[0] = op.lo;
+                t[1] = op.hi;
+                t[2] = op.bias;
+            } else {
+                t[0] = s[i][c];
+            }
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    RowScaleFacts f;
+    f.exact = BITS != 4 || __builtin_amdgcn_ballot_w64(!fine) == 0;
+    f.mid = __builtin_amdgcn_ballot_w64(!mid) == 0;
+    return f;
+}
+
+// Group of U peers from k0 on (entries past the last peer repeat it: loads that are not used).
+template <int NW, int C, int U>
+__device__ __forceinline__ void load_group_rows(const PeerTable& P, int k0, uint64_t tile_byte,
+                                                uint32_t (&lane_byte)[C], uint32_t (&w)[U][C][NW])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint8_t* p = P.codes[k0 + u] + tile_byte;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            // an empty statement the optimizer cannot see through keeps the 32-bit lane offset
+            // next to its use (not widened once and for all outside the loop), so that the load
+            // takes the scalar base + 32-bit vector offset address form instead of a 64-bit
+            // vector add per load
+            asm volatile("" : "+v"(lane_byte[c]));
+            load_words<NW>(p + lane_byte[c], w[u][c]);
+        }
+    }
+}
+
+// Adds peers k0 .. k0 + count - 1 (count <= U; PARTIAL = false: count == U) from w.
+// row_tab: the wave's table advanced to this lane's row.
+template <int BITS, int NW, int C, int U, bool FIRST, bool PARTIAL>
+__device__ __forceinline__ void add_group_rows(float (&acc)[C][(EPL<BITS, NW>::value)], const uint32_t (&w)[U][C][NW],
+                                               const float* __restrict__ row_tab, int k0, int count)
+{
+    using T = RowTable<BITS, C>;
+    const float* t = row_tab + k0 * T::PL;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (PARTIAL && u >= count) break;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const float* tc = t + c * 4 * T::row_pitch + u * T::PL;
+            if (BITS == 4) {
+                Dec4 op;
+                op.lo = tc[0];
+                op.hi = tc[1];
+                op.bias = tc[2];
+#pragma unroll
+                for (int j = 0; j < NW; ++j) {
+                    if (FIRST && u == 0) add_nibbles8<true>(acc[c] + j * 8, w[u][c][j], op);
+                    else add_nibbles8<false>(acc[c] + j * 8, w[u][c][j], op);
+                }
+            } else {
+                if (FIRST && u == 0) accumulate_plain<BITS, NW, true>(acc[c], w[u][c], tc[0]);
+                else accumulate_plain<BITS, NW, false>(acc[c], w[u][c], tc[0]);
+            }
+        }
+    }
+}
+
+// acc[c][*] = sum over the K >= 1 peers, ascending, of the decoded values of the lane's
+// vectors.  Returns true if the wave knows that every nonzero sum lies in [2^-53, 2^69).  tile_byte: byte offset of the wave's tile in every peer's codes; lane_byte[c]:
+// byte offset of the lane's vector c inside the tile; elem[c] / blk[c]: its first element
+// and its block.  tab: LDS for this wave's table.
+template <int BITS, int NW, int C, int U>
+__device__ __forceinline__ bool reduce_rows(const PeerTable& P, int K, uint64_t tile_byte,
+                                            uint32_t (&lane_byte)[C], const uint64_t (&elem)[C],
+                                            const uint64_t (&blk)[C], int lane, float* __restrict__ tab,
+                                            float (&acc)[C][(EPL<BITS, NW>::value)])
+{
+    uint32_t wa[U][C][NW], wb[U][C][NW];
+    const int n = (K + U - 1) / U;  // groups
+    // Issue order: the table's scale pointers, the first group's codes and the lanes' own scales
+    // for it, the table's scales, the second group's codes.  The first group is decoded with the
+    // lanes' own scales while the table's fetches are still on their way.
+    const float* sp[kRowChunks];
+    row_scale_pointers(P, lane, sp);
+    load_group_rows<NW, C, U>(P, 0, tile_byte, lane_byte, wa);
+    float s0[U][C];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < C; ++c) s0[u][c] = P.scales[u][blk[c]];
+    // (both also when there is only one group: the pointer table is padded, and fetches that
+    // depend on nothing later keep this order)
+    float st[kRowChunks][C];
+    row_scale_loads<C>(sp, blk, st);
+    load_group_rows<NW, C, U>(P, U, tile_byte, lane_byte, wb);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (u >= K) break;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (u == 0) accumulate<BITS, NW, true>(acc[c], wa[u][c], s0[u][c]);
+            else accumulate<BITS, NW, false>(acc[c], wa[u][c], s0[u][c]);
+        }
+    }
+    if (n == 1) return false;
+    const RowScaleFacts facts = write_row_table<BITS, C>(st, lane, tab);
+    if (!facts.exact) {
+        // int4 scales of 2^100 and more: every lane decodes with its own scale loads
+#pragma unroll
+        for (int c = 0; c < C; ++c) reduce_peers_plain<BITS, NW>(P, K, elem[c], blk[c], acc[c]);
+        return false;
+    }
+    const float* row_tab = tab + (lane >> 4) * RowTable<BITS, C>::row_pitch;
+    for (int g = 1;;) {  // group g is in flight towards wb, wa is free
+        if (g + 1 >= n) {
+            add_group_rows<BITS, NW, C, U, false, true>(acc, wb, row_tab, g * U, K - g * U);
+            break;
+        }
+        load_group_rows<NW, C, U>(P, (g + 1) * U, tile_byte, lane_byte, wa);
+        add_group_rows<BITS, NW, C, U, false, false>(acc, wb, row_tab, g * U, U);
+        ++g;  // group g is in flight towards wa, wb is free
+        if (g + 1 >= n) {
+            add_group_rows<BITS, NW, C, U, false, true>(acc, wa, row_tab, g * U, K - g * U);
+            break;
+        }
+        load_group_rows<NW, C, U>(P, (g + 1) * U, tile_byte, lane_byte, wb);
+        add_group_rows<BITS, NW, C, U, false, false>(acc, wa, row_tab, g * U, U);
+        ++g;
+    }
+    return facts.mid;
+}
+
+// Lane geometry of a row-form tile that starts at element `tile` of an m-element tensor.
+// m is a multiple of the block and the block of 16 * E, so a row of 16 lanes is inside the
+// tensor or outside it as a whole.  Rows outside repeat the addresses of the tile's first
+// row (always inside): they load valid data and store nothing.
+template <int BITS, int NW, int C>
+struct RowGeometry {
+    static constexpr int E = EPL<BITS, NW>::value;
+    bool ok[C];
+    uint32_t lane_byte[C];
+    uint64_t elem[C], blk[C];
+    __device__ __forceinline__ RowGeometry(uint64_t tile, uint64_t m, int log2b, int lane)
+    {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const uint32_t off = (uint32_t)(c * kWave + lane) * E;
+            ok[c] = tile + off < m;
+            const uint32_t o = ok[c] ? off : (uint32_t)(lane & 15) * E;
+            lane_byte[c] = o * BITS / 8;
+            elem[c] = tile + o;
+            blk[c] = elem[c] >> log2b;
+        }
+    }
+};
+
+// bytes of LDS a wave of a row-form kernel needs: its scale table, and for the inter-node
+// stage the 64 x E results of one vector while they are turned for the store
+template <int BITS, int NW, int C, bool TURN>
+struct RowLds {
+    static constexpr int table = RowTable<BITS, C>::floats * 4;
+    static constexpr int turn = TURN ? kWave * EPL<BITS, NW>::value * 4 : 0;
+    static constexpr int bytes = ((table > turn ? table : turn) + 15) / 16 * 16;
+};
+
 // qgz_intra_reduce, power-of-two blocks with EPL <= B <= 64*EPL: a lane owns the EPL
 // consecutive output elements of NW code dwords, B/EPL lanes form a block.
 template <int BITS, int LOG2B, int NW>
@@ -785,7 +1013,7 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
     const bool ok = e < m;  // m % B == 0 and B % E == 0: a lane is all in or all out
     float acc[E];
     if (ok) {
-        reduce_peers<BITS, NW, ZPP_RED_U, ZPP_RED_PREFETCH>(P, K, e, e >> LOG2B, acc);
+        reduce_peers<BITS, NW, 4>(P, K, e, e >> LOG2B, acc);
     } else {
 #pragma unroll
         for (int i = 0; i < E; ++i) acc[i] = 0.0f;
@@ -862,17 +1090,126 @@ __global__ __launch_bounds__(kWave) void k_intra_reduce_anyblock(const PeerTable
     }
 }
 
-// qgz_inter_reduce: element-wise, the block only selects the scale.  A lane sums
-// the EPL consecutive elements of its 16-byte code vectors; the wave then turns
-// its 64 x EPL results through LDS so that each store instruction writes one
-// contiguous run of 1 KB (lane l, store j: floats 4*(64j + l) .. +4 of the tile).
-template <int BITS, int NW>
-__global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, int K, uint64_t m, uint32_t B,
-                                                           int log2b, float divisor, float recip, float* __restrict__ out)
+// How the inter-node stage divides its sums by the launch's divisor d (same in every lane).
+enum DivMode {
+    kDivIeee = 0,     // the division instruction sequence
+    kDivPow2 = 1,     // d is a power of two: multiplying by its (exact) reciprocal rounds the same real number
+    kDivConstant = 2  // y = RN(1/d) prepared on the host, sums known to lie in a middle range: div_by_constant
+};
+
+// a / d, correctly rounded, from y = RN(1/d): q = a*y; then twice r = a - d*q (exact in a fused
+// multiply-add), q += r*y.  These are the closing steps of the usual division sequence (an
+// approximate quotient from a reciprocal good to an ulp, corrected twice by its exact
+// remainder); with the reciprocal itself correctly rounded and no scaling needed they are
+// all that is left: 5 operations instead of 11.  Valid while nothing under- or overflows: the
+// host admits 2^-10 <= d <= 2^16 and the kernel a = 0 or 2^-53 <= |a| < 2^69, so that
+// 2^-69 <= |q| < 2^79 and every remainder (a multiple of ulp(d) * ulp(q) >= 2^-125) is
+// representable.  zpp_selfcheck_divide compares it with the division for every such a.
+__device__ __forceinline__ float div_by_constant(float a, float d, float y)
+{
+    float q = a * y;
+    float r = __builtin_fmaf(-d, q, a);
+    q = __builtin_fmaf(r, y, q);
+    r = __builtin_fmaf(-d, q, a);
+    return __builtin_fmaf(r, y, q);
+}
+
+// The wave's 64 x E fp32 results of one vector (acc of lane l = elements l*E .. l*E+E-1 of the
+// run that starts at out_run), divided, are turned through LDS so that each store
+// instruction writes one contiguous run of 1 KB (lane l, store j: floats 4*(64j + l) .. +4).
+// Chunk i of lane l is parked in row l at column i ^ (l % CH): rows are read back whole,
+// and lanes writing the same chunk index spread over the columns.  `chunks`: 16-byte
+// chunks of the run that exist (the rest lies past the end of the tensor).
+template <int E>
+__device__ __forceinline__ void store_turned(float (&acc)[E], float divisor, float recip, int mode,
+                                             f32x4* __restrict__ turn, float* __restrict__ out_run, uint64_t chunks,
+                                             int lane)
+{
+    constexpr int CH = E / 4;  // 16-byte chunks of results per lane
+    if (mode == kDivPow2) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = acc[i] * recip;
+    } else if (mode == kDivConstant) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = div_by_constant(acc[i], divisor, recip);
+    } else {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = acc[i] / divisor;
+    }
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        f32x4 v = {acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
+        turn[lane * CH + (i ^ (lane & (CH - 1)))] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    f32x4* o = reinterpret_cast<f32x4*>(out_run);
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const uint32_t c = (uint32_t)j * kWave + lane;  // chunk of the run this lane stores now
+        const uint32_t src_lane = c / CH, src_i = c % CH;
+        const f32x4 v = turn[src_lane * CH + (src_i ^ (src_lane & (CH - 1)))];
+        if (c < chunks) st_stream(v, o + c);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Self-check of div_by_constant against the division: every a with 2^-53 <= |a| < 2^69 (both
+// signs; 122 exponents x 2^23 mantissas, a grid-stride walk) and a = 0; *count += mismatches.
+__global__ __launch_bounds__(kThreads) void k_selfcheck_divide(float d, float y, unsigned long long* __restrict__ count)
+{
+    const uint32_t lo = (127u - 53u) << 23, hi = (127u + 69u) << 23;  // bit patterns of 2^-53 and 2^69
+    unsigned long long bad = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i <= 2ull * (hi - lo); i += (uint64_t)gridDim.x * kThreads) {
+        float a = 0.0f;
+        if (i > 0) {
+            const uint64_t j = i - 1;
+            a = as_f32((uint32_t)(lo + (j >> 1)) | ((uint32_t)(j & 1) << 31));
+        }
+        if (as_u32(div_by_constant(a, d, y)) != as_u32(a / d)) ++bad;
+    }
+    if (bad) atomicAdd(count, bad);
+}
+
+// qgz_inter_reduce, row form: element-wise, the block only selects the scale.  A wave sums
+// C vectors of 64 x E elements (a tile of C * 64 * E consecutive elements).
+template <int BITS, int NW, int C, int U>
+__global__ __launch_bounds__(kThreads) void k_inter_reduce_rows(const PeerTable P, int K, uint64_t m, int log2b,
+                                                                float divisor, float recip, int recip_kind,
+                                                                float* __restrict__ out)
 {
     constexpr int E = EPL<BITS, NW>::value;
-    constexpr int CH = E / 4;  // 16-byte chunks of results per lane
-    __shared__ f32x4 turn[kWavesPerWG][kWave * CH];
+    __shared__ __align__(16) unsigned char lds[kWavesPerWG][RowLds<BITS, NW, C, true>::bytes];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t tile = ((uint64_t)blockIdx.x * kWavesPerWG + wave) * ((uint64_t)C * kWave * E);
+    if (tile >= m) return;
+    RowGeometry<BITS, NW, C> g(tile, m, log2b, lane);
+    float acc[C][E];
+    const bool mid = reduce_rows<BITS, NW, C, U>(P, K, tile * BITS / 8, g.lane_byte, g.elem, g.blk, lane,
+                                                 reinterpret_cast<float*>(lds[wave]), acc);
+    const int mode = recip_kind == kDivConstant && !mid ? kDivIeee : recip_kind;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const uint64_t run = tile + (uint64_t)c * kWave * E;  // same in every lane
+        if (run >= m) break;
+        store_turned<E>(acc[c], divisor, recip, mode, reinterpret_cast<f32x4*>(lds[wave]), out + run, (m - run) / 4,
+                        lane);
+    }
+}
+
+// qgz_inter_reduce for any block size: a lane sums the 8 (int4) or 4 (int8) consecutive
+// elements of one code dword per peer and fetches its own scales.
+template <int BITS>
+__global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, int K, uint64_t m, uint32_t B,
+                                                           int log2b, float divisor, float recip, int recip_kind,
+                                                           float* __restrict__ out)
+{
+    constexpr int E = EPL<BITS, 1>::value;
+    __shared__ f32x4 turn[kWavesPerWG][kWave * E / 4];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t wid = (uint64_t)blockIdx.x * kWavesPerWG + wave;
@@ -882,39 +1219,13 @@ __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, in
     const bool ok = e < m;  // m % 32 == 0 and E divides 32: a lane is all in or all out
     float acc[E];
     if (ok) {
-        reduce_peers<BITS, NW, ZPP_RED_U, ZPP_RED_PREFETCH>(P, K, e, log2b >= 0 ? (e >> log2b) : (e / B), acc);
+        reduce_peers<BITS, 1, 4>(P, K, e, log2b >= 0 ? (e >> log2b) : (e / B), acc);
     } else {
 #pragma unroll
         for (int i = 0; i < E; ++i) acc[i] = 0.0f;
     }
-    f32x4* mine = turn[wave];
-    // chunk i of lane l is parked in row l at column i ^ (l % CH): rows are read back
-    // whole, and lanes writing the same chunk index spread over the columns
-    // a power-of-two divisor: multiplying by its (exact) reciprocal rounds the same real number
-    if (recip != 0.0f) {
-#pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] = acc[i] * recip;
-    } else {
-#pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] = acc[i] / divisor;
-    }
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-        f32x4 v = {acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
-        mine[lane * CH + (i ^ (lane & (CH - 1)))] = v;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    f32x4* o = reinterpret_cast<f32x4*>(out + tile);
-    const uint64_t chunks = (m - tile) / 4;  // 16-byte chunks of this tile that exist
-#pragma unroll
-    for (int j = 0; j < CH; ++j) {
-        const uint32_t c = (uint32_t)j * kWave + lane;  // chunk of the tile this lane stores now
-        const uint32_t src_lane = c / CH, src_i = c % CH;
-        const f32x4 v = mine[src_lane * CH + (src_i ^ (src_lane & (CH - 1)))];
-        if (c < chunks) st_stream(v, o + c);
-    }
+    store_turned<E>(acc, divisor, recip, recip_kind == kDivPow2 ? kDivPow2 : kDivIeee, turn[wave], out + tile,
+                    (m - tile) / 4, lane);
 }
 
 // Plain device copy, one 16-byte vector per lane: the measured bandwidth ceiling the
@@ -944,20 +1255,46 @@ int launch_status()
 
 constexpr uint64_t kMaxGrid = 0x7fffffffull;
 
+// wave slots of the chip at full occupancy: 256 CUs x 4 SIMDs x 8 waves
+constexpr uint64_t kWaveSlots = 256ull * 4 * 8;
+
+#ifdef ZPP_DEV_TUNE
+// development builds only: integer overrides from the environment for tuning sweeps
+long dev_tune(const char* name, long dflt)
+{
+    const char* v = getenv(name);
+    return v ? atol(v) : dflt;
+}
+#endif
+
+// quantize launches of at most this many wave tiles issue all of a tile's loads at once
+uint64_t deep_tiles_limit()
+{
+#ifdef ZPP_DEV_TUNE
+    return (uint64_t)dev_tune("ZPP_DEEP_TILES", 2 * kWaveSlots);
+#else
+    return 2 * kWaveSlots;
+#endif
+}
+
 template <int DT, int BITS, int LOG2B>
 int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t L, uint64_t slices, uint32_t X,
                           uint32_t Y, hipStream_t st)
 {
-    constexpr int VMIN = BITS == 8 ? ZPP_QUANT_V8 : ZPP_QUANT_V4;
+    constexpr int VMIN = BITS == 8 ? kQuantV8 : kQuantV4;
     constexpr int V = (1 << LOG2B) / 512 > VMIN ? (1 << LOG2B) / 512 : VMIN;
     const uint64_t tps = (L + 512 * V - 1) / (512 * V);
     const uint64_t tiles = tps * slices;
     int xcd_shift;
     const uint64_t grid = plan_grid((tiles + kWavesPerWG - 1) / kWavesPerWG, xcd_shift);
     if (grid > kMaxGrid || tiles >= (1ull << 32) || slices >= (1ull << 32)) return ZPP_EINVAL;
-    k_quantize<DT, BITS, LOG2B, V><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
-        x, codes, scales, L, make_fastdiv((uint32_t)tps), (uint32_t)tiles, X, make_fastdiv(X * Y), make_fastdiv(Y),
-        xcd_shift);
+    const FastDiv by_tps = make_fastdiv((uint32_t)tps), byT = make_fastdiv(X * Y), byY = make_fastdiv(Y);
+    if (tiles <= deep_tiles_limit())
+        k_quantize<DT, BITS, LOG2B, V, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+            x, codes, scales, L, by_tps, (uint32_t)tiles, X, byT, byY, xcd_shift);
+    else
+        k_quantize<DT, BITS, LOG2B, V, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+            x, codes, scales, L, by_tps, (uint32_t)tiles, X, byT, byY, xcd_shift);
     return launch_status();
 }
 
@@ -999,22 +1336,29 @@ int dispatch_quantize(const void* x, int dtype, int bits, uint8_t* codes, float*
 #undef ZPP_Q
 }
 
-template <int BITS, int NW>
-int launch_intra_nw(const PeerTable& P, int K, uint64_t m, int l2, uint8_t* codes_out, float* scales_out,
-                    hipStream_t st)
+// Code dwords a lane of qgz_intra_reduce takes per peer.  The kernel is bound by the vector
+// ALU, and the widest vectors cost the fewest instructions per element; narrower ones (more,
+// smaller waves) measured slower at every size.
+constexpr int kIntraNW = 4;
+
+template <int BITS>
+int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* codes_out, float* scales_out,
+                 hipStream_t st)
 {
-    constexpr int E = EPL<BITS, NW>::value;
+    constexpr int E = EPL<BITS, kIntraNW>::value;
+    const int l2 = log2_or_neg(B);
+    if (m / B > kMaxGrid) return ZPP_EINVAL;
     const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
     const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
     if (grid > kMaxGrid) return ZPP_EINVAL;
 #define ZPP_I(L2)                                                                                                    \
     case L2:                                                                                                         \
         if constexpr ((1 << L2) >= E && (1 << L2) <= kWave * E) {                                                    \
-            k_intra_reduce<BITS, L2, NW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out); \
+            k_intra_reduce<BITS, L2, kIntraNW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out); \
             return launch_status();                                                                                  \
         }                                                                                                            \
-        return ZPP_EINVAL
-    switch (l2) {
+        break
+    switch (l2) {  // power-of-two blocks of at most one wave
         ZPP_I(5);
         ZPP_I(6);
         ZPP_I(7);
@@ -1022,42 +1366,108 @@ int launch_intra_nw(const PeerTable& P, int K, uint64_t m, int l2, uint8_t* code
         ZPP_I(9);
         ZPP_I(10);
         ZPP_I(11);
-    default: return ZPP_EINVAL;
+    default: break;
     }
 #undef ZPP_I
+    k_intra_reduce_anyblock<BITS><<<dim3((uint32_t)(m / B)), dim3(kWave), 0, st>>>(P, K, B, codes_out, scales_out);
+    return launch_status();
+}
+
+// divisor of qgz_inter_reduce as the kernels take it
+struct Divisor {
+    float d, recip;
+    int kind;  // DivMode the launch may use
+};
+
+Divisor prepare_divisor(float d)
+{
+    Divisor v = {d, 0.0f, kDivIeee};
+    int e = 0;
+    if (frexpf(d, &e) == 0.5f && e >= -125) {  // a power of two with a finite, normal reciprocal
+        v.recip = 1.0f / d;
+        v.kind = kDivPow2;
+    } else if (d >= 0x1p-10f && d <= 0x1p16f) {
+        v.recip = 1.0f / d;  // correctly rounded
+        v.kind = kDivConstant;
+    }
+    return v;
+}
+
+template <int BITS, int C, int U>
+int launch_inter_rows(const PeerTable& P, int K, uint64_t m, int l2, const Divisor& dv, float* out, hipStream_t st)
+{
+    constexpr uint64_t tile = (uint64_t)C * kWave * EPL<BITS, 1>::value;
+    const uint64_t waves = (m + tile - 1) / tile;
+    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+    k_inter_reduce_rows<BITS, 1, C, U><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, l2, dv.d, dv.recip,
+                                                                                      dv.kind, out);
+    return launch_status();
+}
+
+// Vectors per lane (C) for the row form of qgz_inter_reduce over `tiles` wave tiles of 64 x E
+// elements.  The kernel is bound by the vector ALU, so what matters is that every SIMD gets the
+// same number of tiles and that they all start together: a launch that does not fill more
+// than a few residency rounds is cut into waves of C tiles such that all waves are resident
+// at once (one round, no second round that runs nearly empty), choosing the C that leaves
+// the fewest idle tile slots.  Resident waves per SIMD by registers and LDS: 8, 6, 4 for
+// C = 1, 2, 3.  Larger launches take C = 1 and let the dispatcher balance.
+int inter_rows_vectors(uint64_t tiles)
+{
+    constexpr uint64_t simds = 256 * 4;
+    constexpr uint64_t resident[4] = {0, 8, 6, 4};
+    if (tiles <= resident[1] * simds || tiles > 3 * resident[3] * simds) return 1;
+    int best = 1;
+    uint64_t best_cost = ~0ull;
+    for (int c = 1; c <= 3; ++c) {
+        const uint64_t waves = (tiles + c - 1) / c;
+        if (waves > resident[c] * simds) continue;
+        const uint64_t cost = (waves + simds - 1) / simds * c;  // tiles the busiest SIMD works through
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = c;
+        }
+    }
+    return best;
 }
 
 template <int BITS>
-int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* codes_out, float* scales_out,
-                 hipStream_t st)
+int launch_inter(const PeerTable& P, int K, uint64_t m, uint32_t B, const Divisor& dv, float* out, hipStream_t st)
 {
+    constexpr uint32_t E = EPL<BITS, 1>::value;
     const int l2 = log2_or_neg(B);
-    if (m / B > kMaxGrid) return ZPP_EINVAL;
-    if (l2 >= 0) {
-        // fewest code dwords per lane (most waves) for which a block still fits one wave
-        int nw = ZPP_INTRA_NW;
-        while (nw < 4 && B > (uint32_t)(kWave * nw * 32 / BITS)) nw <<= 1;
-        if (B <= (uint32_t)(kWave * nw * 32 / BITS)) {
-            if (nw == 1) return launch_intra_nw<BITS, 1>(P, K, m, l2, codes_out, scales_out, st);
-            if (nw == 2) return launch_intra_nw<BITS, 2>(P, K, m, l2, codes_out, scales_out, st);
-            return launch_intra_nw<BITS, 4>(P, K, m, l2, codes_out, scales_out, st);
-        }
+    if (l2 >= 0 && B >= 16 * E) {  // a row of 16 lanes inside one block: the row form
+        int c = inter_rows_vectors((m + kWave * E - 1) / (kWave * E));
+#ifdef ZPP_DEV_TUNE
+        const int fc = (int)dev_tune("ZPP_INTER_C", 0);
+        if (fc >= 1 && fc <= 3) c = fc;
+#endif
+        // peers per fetch group: 8 where a wave has one vector (more bytes in flight per wave), 4 otherwise
+        if (c == 1) return launch_inter_rows<BITS, 1, 8>(P, K, m, l2, dv, out, st);
+        if (c == 2) return launch_inter_rows<BITS, 2, 4>(P, K, m, l2, dv, out, st);
+        return launch_inter_rows<BITS, 3, 4>(P, K, m, l2, dv, out, st);
     }
-    k_intra_reduce_anyblock<BITS><<<dim3((uint32_t)(m / B)), dim3(kWave), 0, st>>>(P, K, B, codes_out, scales_out);
+    constexpr uint64_t per_wave = (uint64_t)kWave * E;
+    const uint64_t waves = (m + per_wave - 1) / per_wave;
+    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    if (grid > kMaxGrid) return ZPP_EINVAL;
+    k_inter_reduce<BITS><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, B, l2, dv.d, dv.recip, dv.kind, out);
     return launch_status();
 }
 
 int fill_table(PeerTable& P, const void* const* codes_in, const float* const* scales_in, int K)
 {
     if (!codes_in || !scales_in || K < 1 || K > ZPP_MAX_PEERS) return ZPP_EINVAL;
-    for (int k = 0; k < ZPP_MAX_PEERS; ++k) {
-        P.codes[k] = nullptr;
-        P.scales[k] = nullptr;
-    }
     for (int k = 0; k < K; ++k) {
         if (!codes_in[k] || !scales_in[k] || !aligned(codes_in[k], 16) || !aligned(scales_in[k], 4)) return ZPP_EINVAL;
         P.codes[k] = static_cast<const uint8_t*>(codes_in[k]);
         P.scales[k] = scales_in[k];
+    }
+    // the unused entries repeat the last peer: kernels that fetch peers in fixed groups may read
+    // (and then ignore) them
+    for (int k = K; k < ZPP_MAX_PEERS; ++k) {
+        P.codes[k] = P.codes[K - 1];
+        P.scales[k] = P.scales[K - 1];
     }
     return ZPP_OK;
 }
@@ -1080,7 +1490,6 @@ const char* zpp_strerror(int code)
     case ZPP_OK: return "ok";
     case ZPP_EINVAL: return "invalid argument (null or misaligned pointer, size not a multiple of the block, value out of range)";
     case ZPP_ELAUNCH: return "HIP runtime refused the kernel launch";
-    case ZPP_EUNSUPPORTED: return "combination not supported by this build";
     default: return "unknown zpp error code";
     }
 }
@@ -1132,7 +1541,7 @@ int qwz_dequantize(const void* codes, const float* scales, size_t n, int block, 
     if (!valid_dtype(out_dtype) || !valid_bits(bits) || !valid_block(block) || n % (size_t)block != 0) return ZPP_EINVAL;
     if (n == 0) return ZPP_OK;
     if (!y || !codes || !scales || !aligned(y, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return ZPP_EINVAL;
-    constexpr int V = ZPP_DEQ_V;
+    constexpr int V = kDeqV;
     const uint64_t waves = (n + 512 * V - 1) / (512 * V);
     int xcd_shift;
     const uint64_t grid = plan_grid((waves + kWavesPerWG - 1) / kWavesPerWG, xcd_shift);
@@ -1140,7 +1549,7 @@ int qwz_dequantize(const void* codes, const float* scales, size_t n, int block, 
     const uint8_t* c = static_cast<const uint8_t*>(codes);
     const int l2 = log2_or_neg((uint32_t)block);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool one_block = ZPP_DEQ_ONE_BLOCK && block % (512 * V) == 0;  // a wave's tile inside one block
+    const bool one_block = block % (512 * V) == 0;  // a wave's tile inside one block
 #define ZPP_D(ODT, BITS)                                                                                          \
     do {                                                                                                          \
         if (l2 >= 0 && one_block)                                                                                 \
@@ -1185,21 +1594,9 @@ int qgz_inter_reduce(const void* const* codes_in, const float* const* scales_in,
     if (m == 0) return ZPP_OK;
     if (!out || !aligned(out, 16)) return ZPP_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int l2 = log2_or_neg((uint32_t)block);
-    int dexp = 0;
-    const float recip = (frexpf(divisor, &dexp) == 0.5f && dexp >= -125) ? 1.0f / divisor : 0.0f;
-    // one code dword per lane and peer measured fastest at every size (most waves in
-    // flight; the kernel is bound by latency and issue, not by vector width)
-    constexpr int nw = ZPP_INTER_NW;
-    const uint64_t per_wave = (uint64_t)kWave * nw * (32 / bits);
-    const uint64_t waves = (m + per_wave - 1) / per_wave;
-    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
-    if (grid > kMaxGrid) return ZPP_EINVAL;
-#define ZPP_R(BITS) k_inter_reduce<BITS, ZPP_INTER_NW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, nodes, m, (uint32_t)block, l2, divisor, recip, out)
-    if (bits == 4) ZPP_R(4);
-    else ZPP_R(8);
-#undef ZPP_R
-    return launch_status();
+    const Divisor dv = prepare_divisor(divisor);
+    if (bits == 4) return launch_inter<4>(P, nodes, m, (uint32_t)block, dv, out, st);
+    return launch_inter<8>(P, nodes, m, (uint32_t)block, dv, out, st);
 }
 
 // Diagnostic: compares the short division sequences the encoders use with the plain
@@ -1211,6 +1608,17 @@ int zpp_selfcheck_block_scale(int bits, int exponent, unsigned long long* counts
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (bits == 4) k_selfcheck_block_scale<4><<<dim3((1u << 23) / kThreads), dim3(kThreads), 0, st>>>(eb, counts);
     else k_selfcheck_block_scale<8><<<dim3((1u << 23) / kThreads), dim3(kThreads), 0, st>>>(eb, counts);
+    return launch_status();
+}
+
+// Diagnostic: compares the short division by a launch-constant divisor that qgz_inter_reduce
+// uses with the plain fp32 division, for every dividend the kernel admits to it.
+int zpp_selfcheck_divide(float divisor, unsigned long long* count, void* stream)
+{
+    if (!count || !aligned(count, 8) || !(divisor > 0.0f)) return ZPP_EINVAL;
+    const Divisor dv = prepare_divisor(divisor);
+    if (dv.kind != kDivConstant) return ZPP_EINVAL;  // such divisors never take the short sequence
+    k_selfcheck_divide<<<dim3(256 * 32), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(dv.d, dv.recip, count);
     return launch_status();
 }
 

@@ -8,9 +8,9 @@ device copy of the gathered codes.
 
 * QgzPipeline: the gradient is cut into S pipeline stages; stage s's
   dequantize -> reduce -> quantize (intra-node hop) runs on one stream while
-  stage s-1's dequantize -> reduce (inter-node hop) runs on another (the paper's
-  Fig. "pipelining and overlapping intra-node with inter-node communication";
-  the slice order for S stages is the generalized reordering of Alg. 2).
+  stage s-1's dequantize -> reduce (inter-node hop) runs on another (Sec. 4.1, the
+  pipelining figure; the slice order for S stages is the generalized reordering of
+  Alg. 2).
 * QwzPrefetch: layer k+1's own-shard quantization is enqueued on a side stream
   while layer k's (stand-in) all-gather and dequantization run on the main
   stream; the main stream waits on an event only where it needs layer k+1's
@@ -157,7 +157,7 @@ class QwzPrefetch:
             if side is not main:
                 main.wait_event(ready[k])
             slot = k % 2
-            zpp.stream_copy(self.recv_codes, self.gather_codes[slot])          # stand-in all-gather
+            self.recv_codes.copy_(self.gather_codes[slot], non_blocking=True)   # stand-in all-gather
             self.recv_scales.copy_(self.gather_scales[slot], non_blocking=True)
             gathered = torch.cuda.Event()
             gathered.record(main)

@@ -1,5 +1,5 @@
 """The C-ABI library loads on a machine without a GPU and exports every symbol
-that include/zpp.h declares; the host-only helpers behave as documented."""
+that include/*.h declare; the host-only helpers behave as documented."""
 import ctypes
 import os
 import re
@@ -11,8 +11,8 @@ from paper_2306_10209_amd import binding as zpp
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "zpp.h")).read()
+def declared_functions(header="zpp.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"^\s*(?:const\s+)?[A-Za-z_][\w\s\*]*?\b(\w+)\s*\([^;{]*\)\s*;", text, flags=re.M)
     return sorted(set(names))
@@ -28,8 +28,16 @@ def test_header_declares_the_five_operations():
 def test_library_exports_every_declared_symbol():
     assert os.path.exists(zpp.LIB_PATH), "build the library first: python -m paper_2306_10209_amd.build"
     lib = ctypes.CDLL(zpp.LIB_PATH)
-    for name in declared_functions():
-        assert hasattr(lib, name), name
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        names = declared_functions(header)
+        assert names, header
+        for name in names:
+            assert hasattr(lib, name), (header, name)
+
+
+def test_diagnostics_header_matches_its_binding():
+    from paper_2306_10209_amd import diagnostics
+    assert set(diagnostics.EXPORTS) == set(declared_functions("zpp_diagnostics.h"))
 
 
 def test_size_helpers():
@@ -87,7 +95,8 @@ def test_sizes_beyond_the_launch_limits_are_rejected_on_the_host():
     assert L.qgz_intra_reduce(table, table, 2, huge, 512, 4, fake, fake, None) == -1
     assert L.qgz_intra_reduce(table, table, 2, 96 << 40, 96, 4, fake, fake, None) == -1
     assert L.qgz_inter_reduce(table, table, 2, huge, 512, 4, ctypes.c_float(2.0), fake, None) == -1
-    assert L.zpp_stream_copy(fake, fake, 1 << 60, None) == -1
+    from paper_2306_10209_amd import diagnostics
+    assert diagnostics._lib().zpp_stream_copy(fake, fake, 1 << 60, None) == -1
 
 
 def test_reorder_helpers_equal_oracle_on_many_shapes():
