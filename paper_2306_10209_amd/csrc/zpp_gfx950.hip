@@ -773,14 +773,15 @@ __device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, ui
 // issued before the current group is decoded; every branch of the steady state leaves
 // the loop, so the wait before a decode never includes the loads issued after it.
 
-// One wave's table: [vector c][row r][peer k][operand], PL operands per peer (int4: s * 2^24,
-// s * 2^20, -8 s; int8: s).  The row pitch is odd, so the 4 rows, which are read together,
-// fall into different banks.
+// One wave's table: [row r][peer k][vector c][operand], PL operands per peer and vector (int4:
+// s * 2^24, s * 2^20, -8 s; int8: s), so that what one peer needs, and what a group of peers
+// needs, is one short run behind one address.  The row pitch is odd, so the 4 rows, which are
+// read together, fall into different banks.
 template <int BITS, int C>
 struct RowTable {
     static constexpr int PL = BITS == 4 ? 3 : 1;
-    static constexpr int row_pitch = (ZPP_MAX_PEERS * PL) | 1;
-    static constexpr int floats = C * 4 * row_pitch;
+    static constexpr int row_pitch = (ZPP_MAX_PEERS * C * PL) | 1;
+    static constexpr int floats = 4 * row_pitch;
 };
 
 // The wave's table is filled in three steps, so that the two dependent fetches it needs can be
@@ -824,7 +825,7 @@ __device__ __forceinline__ RowScaleFacts write_row_table(const float (&s)[kRowCh
     for (int i = 0; i < kRowChunks; ++i)
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            float* t = tab + (c * 4 + row) * T::row_pitch + (i * 16 + j) * T::PL;
+            float* t = tab + row * T::row_pitch + ((i * 16 + j) * C + c) * T::PL;
             const float mag = fabsf(s[i][c]);
             mid = mid && (mag == 0.0f || (mag >= 0x1p-30f && mag < 0x1p60f));
             if (BITS == 4) {
@@ -873,13 +874,13 @@ __device__ __forceinline__ void add_group_rows(float (&acc)[C][(EPL<BITS, NW>::v
                                                const float* __restrict__ row_tab, int k0, int count)
 {
     using T = RowTable<BITS, C>;
-    const float* t = row_tab + k0 * T::PL;
+    const float* t = row_tab + k0 * (C * T::PL);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (PARTIAL && u >= count) break;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            const float* tc = t + c * 4 * T::row_pitch + u * T::PL;
+            const float* tc = t + (u * C + c) * T::PL;
             if (BITS == 4) {
                 Dec4 op;
                 op.lo = tc[0];
@@ -1179,13 +1180,20 @@ __global__ __launch_bounds__(kThreads) void k_selfcheck_divide(float d, float y,
 template <int BITS, int NW, int C, int U>
 __global__ __launch_bounds__(kThreads) void k_inter_reduce_rows(const PeerTable P, int K, uint64_t m, int log2b,
                                                                 float divisor, float recip, int recip_kind,
+                                                                uint32_t groups_per_xcd, int xcd_shift,
                                                                 float* __restrict__ out)
 {
     constexpr int E = EPL<BITS, NW>::value;
     __shared__ __align__(16) unsigned char lds[kWavesPerWG][RowLds<BITS, NW, C, true>::bytes];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t tile = ((uint64_t)blockIdx.x * kWavesPerWG + wave) * ((uint64_t)C * kWave * E);
+    // Workgroup b runs on XCD b % 8.  Tiles are handed out so that a cache line of scales (32
+    // consecutive blocks of one peer) is fetched into one XCD's L2, not into all eight: a small
+    // grid gives each XCD one contiguous eighth of the tiles (groups_per_xcd > 0), a large one
+    // runs of consecutive tiles, with all XCDs moving through the tensor together.
+    const uint64_t group = groups_per_xcd ? (uint64_t)(blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3)
+                                          : logical_block(xcd_shift);
+    const uint64_t tile = (group * kWavesPerWG + wave) * ((uint64_t)C * kWave * E);
     if (tile >= m) return;
     RowGeometry<BITS, NW, C> g(tile, m, log2b, lane);
     float acc[C][E];
@@ -1398,10 +1406,17 @@ int launch_inter_rows(const PeerTable& P, int K, uint64_t m, int l2, const Divis
 {
     constexpr uint64_t tile = (uint64_t)C * kWave * EPL<BITS, 1>::value;
     const uint64_t waves = (m + tile - 1) / tile;
-    const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    const uint64_t groups = (waves + kWavesPerWG - 1) / kWavesPerWG;
+    // surplus groups of either padded grid exit at once
+    int xcd_shift;
+    uint64_t per_xcd = 0, grid = plan_grid(groups, xcd_shift);
+    if (xcd_shift < 0) {
+        per_xcd = (groups + 7) / 8;
+        grid = per_xcd * 8;
+    }
     if (grid > kMaxGrid) return ZPP_EINVAL;
-    k_inter_reduce_rows<BITS, 1, C, U><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, l2, dv.d, dv.recip,
-                                                                                      dv.kind, out);
+    k_inter_reduce_rows<BITS, 1, C, U><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+        P, K, m, l2, dv.d, dv.recip, dv.kind, (uint32_t)per_xcd, xcd_shift, out);
     return launch_status();
 }
 
