@@ -16,6 +16,7 @@ Inputs are seeded synthetic tensors resident in HBM before the timed region.
 Prints ONE JSON line; `value` is algorithmic bytes per second over the whole step.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -28,6 +29,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9   # plain (unpacked) vector-ALU lane-operations per second
 METRIC = "effective HBM GB/s (and % of peak) per qwZ/qgZ kernel at 1 MI355X"
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2306_10209_amd", "csrc", "zpp_gfx950.hip")
 
 
 def parse():
@@ -42,6 +44,7 @@ def parse():
                     help="skip the timings of the Sec. 4.1 launch schedules (pipeline stages, weight prefetch)")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the per-kernel timings at the shapes of the other configurations")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replays of the step")
     ap.add_argument("--cpu-sample-div", type=int, default=1,
                     help="the CPU oracle is timed on 1/div of one layer")
     return ap.parse_args()
@@ -65,6 +68,33 @@ class Bytes:
     @staticmethod
     def inter(m, B, bits, Y):
         return Y * (m * bits // 8 + 4 * (m // B)) + 4 * m
+
+
+def profile_figures(name, kernel, elements):
+    """Per-launch figures of `kernel` from a committed rocprofv3 counter summary under profiles/.
+    They are measurements of an earlier run, so they are handed out only with their source
+    attached and only if the summary says it was taken from this very kernel source (sha256 of
+    the .hip file) at this problem size; otherwise the reason is returned instead."""
+    path = os.path.join(ROOT, "profiles", name)
+    src = {"file": f"profiles/{name}"}
+    if not os.path.exists(path):
+        return None, dict(src, refused="summary not present")
+    want_hash = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+    facts, rows = {}, {}
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == "SOURCE":
+            facts.update(p.split("=", 1) for p in parts[1:] if "=" in p)
+        if len(parts) >= 3 and parts[0] in ("TRAFFIC", "VALU"):
+            rows[parts[1]] = dict(p.split("=", 1) for p in parts[2:] if "=" in p)
+    if facts.get("sha256") != want_hash:
+        return None, dict(src, refused="summary was taken from another version of the kernel source")
+    row = rows.get(kernel)
+    if row is None:
+        return None, dict(src, refused=f"no row for {kernel}")
+    if int(row.get("elements", -1)) != elements:
+        return None, dict(src, refused="summary was taken at another problem size")
+    return row, dict(src, kernel=row.get("kernel"), grid_threads=int(row.get("grid_threads", 0)), elements=elements)
 
 
 def main():
@@ -140,15 +170,26 @@ def main():
         "qgz_intra_reduce": Bytes.intra(m, GB_, GBITS, X),
         "qgz_inter_reduce": Bytes.inter(L, GB_, GBITS, Y),
     }
+    elements_per = {"qwz_dequantize": n_L, "qwz_quantize": L, "qgz_reorder": n_L, "qgz_intra_reduce": m,
+                    "qgz_inter_reduce": L}
     calls_per_step = {"qwz_dequantize": 2 * layers, "qwz_quantize": layers, "qgz_reorder": layers,
                       "qgz_intra_reduce": layers, "qgz_inter_reduce": layers}
     step_bytes = sum(bytes_per[k] * calls_per_step[k] for k in bytes_per)
+
+    launch = {
+        "qwz_dequantize": lambda l: zpp.qwz_dequantize(wcodes, wscales, n_L, WB, WBITS, out=wout),
+        "qgz_reorder": lambda l: zpp.qgz_reorder(grad, X, Y, 1, GB_, GBITS, codes=gcodes, scales=gscales),
+        "qgz_intra_reduce": lambda l: zpp.qgz_intra_reduce(intra_tables[l % 2], None, m, GB_, GBITS, codes_out=icodes,
+                                                           scales_out=iscales),
+        "qgz_inter_reduce": lambda l: zpp.qgz_inter_reduce(inter_tables[l % 8], None, L, GB_, GBITS, float(W), out=gout),
+        "qwz_quantize": lambda l: zpp.qwz_quantize(own, WB, WBITS, codes=own_codes, scales=own_scales),
+    }
 
     events = {k: [] for k in bytes_per}
     DOM = "qwz_dequantize"
     counter = [0]
 
-    def timed(name, fn, record):
+    def timed(name, l, record):
         """record: "all" brackets every launch with HIP events; "sparse" only every fourth launch
         of the dominant kernel (an event pair costs a few microseconds of queue time, and the
         timed region should pay as little of that as possible)."""
@@ -156,22 +197,18 @@ def main():
         if record == "all" or (record == "sparse" and name == DOM and counter[0] % 4 == 0):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-            fn()
+            launch[name](l)
             b.record()
             events[name].append((a, b))
         else:
-            fn()
+            launch[name](l)
 
     def step(record):
-        for _ in range(layers):                                   # forward
-            timed("qwz_dequantize", lambda: zpp.qwz_dequantize(wcodes, wscales, n_L, WB, WBITS, out=wout), record)
+        for l in range(layers):                                   # forward
+            timed("qwz_dequantize", l, record)
         for l in reversed(range(layers)):                         # backward
-            timed("qwz_dequantize", lambda: zpp.qwz_dequantize(wcodes, wscales, n_L, WB, WBITS, out=wout), record)
-            timed("qgz_reorder", lambda: zpp.qgz_reorder(grad, X, Y, 1, GB_, GBITS, codes=gcodes, scales=gscales), record)
-            it, nt = intra_tables[l % 2], inter_tables[l % 8]
-            timed("qgz_intra_reduce", lambda: zpp.qgz_intra_reduce(it, None, m, GB_, GBITS, codes_out=icodes, scales_out=iscales), record)
-            timed("qgz_inter_reduce", lambda: zpp.qgz_inter_reduce(nt, None, L, GB_, GBITS, float(W), out=gout), record)
-            timed("qwz_quantize", lambda: zpp.qwz_quantize(own, WB, WBITS, codes=own_codes, scales=own_scales), record)
+            for name in ("qwz_dequantize", "qgz_reorder", "qgz_intra_reduce", "qgz_inter_reduce", "qwz_quantize"):
+                timed(name, l, record)
 
     for _ in range(args.warmup):
         step(None)
@@ -192,16 +229,6 @@ def main():
     for _ in range(2):
         step("all")
     torch.cuda.synchronize()
-    # vector-ALU instructions per launch measured with rocprofv3 --pmc SQ_INSTS_VALU (committed
-    # summary); one wave64 instruction is 64 lane-operations, the chip retires 256 CUs x 4 SIMDs x
-    # 16 lanes x 2.4 GHz = 39.3e12 of them per second
-    valu = {}
-    vpath = os.path.join(ROOT, "profiles", "bench_step_valu.txt")
-    if os.path.exists(vpath):
-        for line in open(vpath):
-            parts = line.split()
-            if len(parts) == 3 and parts[0] == "VALU":
-                valu[parts[1]] = int(parts[2].split("=")[1])
     kernels = {}
     for k, ev in events.items():
         ms = [a.elapsed_time(b) for a, b in ev]
@@ -209,11 +236,43 @@ def main():
         gbs = bytes_per[k] / (avg * 1e-3) / 1e9
         kernels[k] = {"bytes": bytes_per[k], "avg_ms": round(avg, 5), "min_ms": round(min(ms), 5),
                       "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                      "launches": len(ms)}
-        if k in valu:
-            alu = valu[k] * 64 / (avg * 1e-3)
+                      "launches": len(ms), "protocol": "one launch between two HIP events, inside the step"}
+        # vector-ALU instructions per launch from a committed rocprofv3 --pmc SQ_INSTS_VALU summary: one
+        # wave64 instruction is 64 lane-operations; the chip retires 256 CUs x 4 SIMDs x 16 lanes x
+        # 2.4 GHz = 39.3e12 of them per second at its peak clock
+        row, source = profile_figures("bench_step_valu.txt", k, elements_per[k])
+        if row is not None:
+            alu = int(row["valu_insts"]) * 64 / (avg * 1e-3)
             kernels[k]["frac_of_alu_peak"] = round(alu / ALU_PEAK_LANE_OPS, 4)
             kernels[k]["bound"] = "alu" if alu / ALU_PEAK_LANE_OPS > gbs / HBM_PEAK_GBS else "hbm"
+            kernels[k]["valu_insts_per_launch"] = int(row["valu_insts"])
+            kernels[k]["valu_source"] = source
+        else:
+            kernels[k]["valu_source"] = source
+
+    # the same step captured once into a HIP graph (kernel nodes only) and replayed
+    graph = None
+    if not args.no_graph:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream(device=dev)
+        side.wait_stream(torch.cuda.current_stream(dev))
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                step(None)
+        torch.cuda.current_stream(dev).wait_stream(side)
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        g_el = time.perf_counter() - t2
+        graph = {"graph_ms_per_step": round(g_el * 1e3 / args.steps, 3),
+                 "graph_GBps": round(step_bytes / (g_el / args.steps) / 1e9, 1),
+                 "eager_ms_per_step": round(ms_per_step, 3), "kernel_nodes": sum(calls_per_step.values()),
+                 "note": "the eager step is `value`; the step is not bound by launch rate"}
+        del g
 
     # measured copy ceiling: 2 GiB read + 2 GiB written per launch
     src = grad.view(torch.uint8)[: 1 << 31]
@@ -232,27 +291,33 @@ def main():
     copy_gbs = 2 * (1 << 31) / (copy_ms * 1e-3) / 1e9
 
     dom = DOM
-    # HBM bytes per launch measured with rocprofv3 --pmc (committed summary, see profiles/)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "bench_step_hbm_traffic.txt")
-    if os.path.exists(tpath):
-        for line in open(tpath):
-            parts = line.split()
-            if len(parts) == 3 and parts[0] == "TRAFFIC" and parts[1] == dom:
-                traffic = int(parts[2].split("=")[1])
+    # HBM bytes per launch from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary
+    row, traffic_source = profile_figures("bench_step_hbm_traffic.txt", dom, elements_per[dom])
+    traffic = int(row["bytes_per_launch"]) if row is not None else None
     dom_gbs = bytes_per[dom] / (dom_avg * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": traffic_source,
                 "algorithmic_bytes_per_launch": bytes_per[dom], "avg_launch_ms": round(dom_avg, 5),
                 "launches_timed": dom_launches, "copy_ceiling_GBps": round(copy_gbs, 1)}
+
+    runner = Runner(torch, diagnostics, dev)
+    # each kernel of the step alone, at the step's shapes and operands, in batches of back-to-back launches
+    step_shapes = {}
+    it = [0]
+    for name in bytes_per:
+        def one(name=name):
+            it[0] += 1
+            launch[name](it[0])
+        step_shapes[name] = runner.run(bytes_per[name], one, batch=10 if bytes_per[name] < 2e9 else 4)
 
     schedules = None
     if not args.no_schedules:
         schedules = schedule_timings(torch, zpp, dev, n_L, X, Y, W, GB_, GBITS, WB, WBITS, grad, peer_sets[0],
                                      node_sets[0], own, wcodes, wscales, wout)
-    del w, wout, grad, gcodes, gscales, peer_sets, node_sets, wcodes, src, dst, intra_tables, inter_tables
+    del w, wout, grad, gcodes, gscales, peer_sets, node_sets, wcodes, src, dst, intra_tables, inter_tables, launch
     torch.cuda.empty_cache()
-    per_config = None if args.no_configs else per_config_kernels(torch, zpp, workloads, dev)
+    per_config = None if args.no_configs else per_config_kernels(torch, zpp, workloads, dev, runner)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -268,72 +333,33 @@ def main():
                    "layers": layers, "hidden": args.hidden, "elements_per_layer": n_L,
                    "step_algorithmic_bytes": step_bytes, "calls_per_step": calls_per_step},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "other_configs": per_config,
+        "roofline": roofline, "cpu_baseline": cpu, "graph": graph, "kernels": kernels,
+        "kernels_alone_at_step_shapes": step_shapes, "other_configs": per_config,
         "schedules": schedules,
         "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))
 
 
-def schedule_timings(torch, zpp, dev, n_L, X, Y, W, GB_, GBITS, WB, WBITS, grad, peers, nodes, own, wcodes, wscales,
-                     wout):
-    """Sec. 4.1 schedules at the benchmark's layer size: (a) the gradient path of one layer cut
-    into S pipeline stages, on one stream and with the two hops on two streams; (b) eight layers
-    of the forward weight path with the next layer's shard quantization on a side stream."""
-    from paper_2306_10209_amd.schedule import QgzPipeline, QwzPrefetch
+class Runner:
+    """Timing protocol of everything outside the timed step: HIP events on the launch stream around
+    `batch` back-to-back launches, >= 3 warm-up launches, `rounds` batches, median / min / max of the
+    per-launch time.  A 1 GiB copy is queued in front of each batch so that the host is ahead of the
+    GPU when the first event is reached: short kernels are then timed at the GPU's pace, not the
+    host's.  Callers rotate their operands so that inputs do not stay in the 256 MB last-level cache."""
 
-    def time_ms(fn, reps=5):
-        fn()
-        ev = []
-        for _ in range(reps):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            fn()
-            b.record()
-            ev.append((a, b))
-        torch.cuda.synchronize()
-        ms = sorted(x.elapsed_time(y) for x, y in ev)
-        return round(ms[len(ms) // 2], 4)
+    def __init__(self, torch, diagnostics, dev):
+        self.torch, self.diagnostics = torch, diagnostics
+        self.blk_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        self.blk_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
 
-    res = {"qgz_pipeline_ms_per_layer": {}, "qwz_prefetch_ms_8_layers": {}}
-    nc, ns = nodes
-    out = torch.empty(n_L // W, dtype=torch.float32, device=dev)
-    for S in (1, 2, 4):
-        for two in (False, True):
-            pipe = QgzPipeline(n_L, X, Y, S, GB_, GBITS, device=dev, two_streams=two)
-            pipe.bind(0, 0, peers, list(zip(nc, ns)))
-            res["qgz_pipeline_ms_per_layer"][f"S={S},{'two_streams' if two else 'one_stream'}"] = \
-                time_ms(lambda: pipe.run(grad, out, float(W)))
-            del pipe
-    L = n_L // W
-    for overlap in (False, True):
-        sched = QwzPrefetch(n_L, L, 0, WB, WBITS, device=dev, overlap=overlap)
-        for slot in range(2):
-            sched.gather_codes[slot].copy_(wcodes)
-            sched.gather_scales[slot].copy_(wscales)
-        res["qwz_prefetch_ms_8_layers"]["overlapped" if overlap else "serial"] = \
-            time_ms(lambda: sched.run([own] * 8, [wout] * 8))
-        del sched
-    return res
-
-
-def per_config_kernels(torch, zpp, workloads, dev):
-    """Each kernel alone at the shapes of configs[0..3], HIP events on the launch stream,
-    GB/s of algorithmic bytes (see run() for the protocol)."""
-    res = {}
-
-    blk_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    blk_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-
-    def run(name, nbytes, fn, note=None, batch=10, rounds=7):
-        """Median over `rounds` of (time of `batch` back-to-back launches) / batch.  A 1 GiB copy
-        is queued in front of each batch so that the host is ahead of the GPU when the first
-        event is reached: short kernels are then timed at the GPU's pace, not the host's."""
-        for _ in range(3):
+    def times(self, fn, batch=10, rounds=7, warm=3):
+        torch = self.torch
+        for _ in range(warm):
             fn()
         ev = []
         for _ in range(rounds):
-            diagnostics.stream_copy(blk_dst, blk_src)
+            self.diagnostics.stream_copy(self.blk_dst, self.blk_src)
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             for _ in range(batch):
@@ -341,13 +367,80 @@ def per_config_kernels(torch, zpp, workloads, dev):
             b.record()
             ev.append((a, b))
         torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) / batch for a, b in ev)
+        return sorted(a.elapsed_time(b) / batch for a, b in ev)
+
+    def run(self, nbytes, fn, note=None, batch=10, rounds=7, launches=1):
+        ms = self.times(fn, batch, rounds)
         med = ms[len(ms) // 2]
         gbs = nbytes / (med * 1e-3) / 1e9
-        res[name] = {"bytes": int(nbytes), "median_us": round(med * 1e3, 2), "min_us": round(ms[0] * 1e3, 2),
-                     "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        res = {"bytes": int(nbytes), "median_us": round(med * 1e3, 2), "min_us": round(ms[0] * 1e3, 2),
+               "max_us": round(ms[-1] * 1e3, 2), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+               "launches_per_sample": batch * launches, "samples": rounds}
         if note:
-            res[name]["note"] = note
+            res["note"] = note
+        return res
+
+
+def schedule_timings(torch, zpp, dev, n_L, X, Y, W, GB_, GBITS, WB, WBITS, grad, peers, nodes, own, wcodes, wscales,
+                     wout):
+    """Sec. 4.1 schedules at the benchmark's layer size: (a) the gradient path of one layer cut
+    into S pipeline stages, on one stream and with the two hops on two streams; (b) eight layers
+    of the forward weight path with the next layer's shard quantization on a side stream.
+    Protocol: all variants of a family are built first and then timed interleaved (variant 1,
+    2, ..., variant 1, 2, ...), 3 warm-up rounds, 20 timed rounds; every variant moves several GB
+    per run, so between two runs of one variant the last-level cache has been turned over many
+    times.  min / median / max in ms."""
+    from paper_2306_10209_amd.schedule import QgzPipeline, QwzPrefetch
+
+    def interleaved(variants, warm=3, reps=20):
+        for _ in range(warm):
+            for fn in variants.values():
+                fn()
+        ev = {k: [] for k in variants}
+        for _ in range(reps):
+            for k, fn in variants.items():
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                ev[k].append((a, b))
+        torch.cuda.synchronize()
+        out = {}
+        for k, pairs in ev.items():
+            ms = sorted(a.elapsed_time(b) for a, b in pairs)
+            out[k] = {"min": round(ms[0], 4), "median": round(ms[len(ms) // 2], 4), "max": round(ms[-1], 4)}
+        return out
+
+    res = {"protocol": "variants interleaved, 3 warm-up rounds, 20 timed rounds, HIP events; ms"}
+    nc, ns = nodes
+    out = torch.empty(n_L // W, dtype=torch.float32, device=dev)
+    pipes = {}
+    for S in (1, 2, 4):
+        for two in (False, True):
+            pipe = QgzPipeline(n_L, X, Y, S, GB_, GBITS, device=dev, two_streams=two)
+            pipe.bind(0, 0, peers, list(zip(nc, ns)))
+            pipes[f"S={S},{'two_streams' if two else 'one_stream'}"] = pipe
+    res["qgz_pipeline_ms_per_layer"] = interleaved({k: (lambda p=p: p.run(grad, out, float(W))) for k, p in pipes.items()})
+    del pipes
+    L = n_L // W
+    scheds = {}
+    for overlap in (False, True):
+        sched = QwzPrefetch(n_L, L, 0, WB, WBITS, device=dev, overlap=overlap)
+        for slot in range(2):
+            sched.gather_codes[slot].copy_(wcodes)
+            sched.gather_scales[slot].copy_(wscales)
+        scheds["overlapped" if overlap else "serial"] = sched
+    res["qwz_prefetch_ms_8_layers"] = interleaved({k: (lambda s=s: s.run([own] * 8, [wout] * 8)) for k, s in scheds.items()})
+    return res
+
+
+def per_config_kernels(torch, zpp, workloads, dev, runner):
+    """Each kernel alone at the shapes of configs[0..3], and the paths for block sizes that are not
+    powers of two; protocol: Runner."""
+    res = {}
+
+    def run(name, nbytes, fn, note=None, **kw):
+        res[name] = runner.run(nbytes, fn, note, **kw)
 
     # configs[0]: one fp16 4096x256 tensor, int8 block 256 (3 MB: launch-latency bound, cache resident)
     n = 1 << 20
@@ -371,34 +464,54 @@ def per_config_kernels(torch, zpp, workloads, dev):
     w = workloads.weights(n_total, device=dev, tensor_id=10)
     codes = torch.empty(n_total, dtype=torch.uint8, device=dev)
     scales = torch.empty(n_total // B, dtype=torch.float32, device=dev)
-    shards, off = [], 0
+    shards, off = [], 0          # (offset, length, simulated rank)
     for _, r, c_ in shapes:
         sh = r * c_ // P
         for rank in range(P):
-            shards.append((off + rank * sh, sh))
+            shards.append((off + rank * sh, sh, rank))
         off += r * c_
 
-    def quantize_layer():
-        for lo, sh in shards:
-            zpp.qwz_quantize(w[lo:lo + sh], B, 8, codes=codes[lo:lo + sh], scales=scales[lo // B:(lo + sh) // B])
+    def quantize_shard(lo, sh, stream=None):
+        zpp.qwz_quantize(w[lo:lo + sh], B, 8, codes=codes[lo:lo + sh], scales=scales[lo // B:(lo + sh) // B], stream=stream)
 
-    run("cfg1.qwz_quantize_32_shards", Bytes.quantize(n_total, B, 8), quantize_layer,
-        "32 launches (8 rank shards x 4 matrices) written at their offsets of the gather buffer", batch=2)
-    # the 8 simulated ranks are independent: the same 32 launches spread over 4 streams
+    def quantize_layer():
+        for lo, sh, _ in shards:
+            quantize_shard(lo, sh)
+
+    nb = Bytes.quantize(n_total, B, 8)
+    run("cfg1.qwz_quantize_32_shards", nb, quantize_layer,
+        "32 launches (8 rank shards x 4 matrices) on one stream, written at their offsets of the gather buffer",
+        batch=2, launches=32)
+    # The 8 simulated ranks are 8 independent processes in the method, so their launches carry no
+    # order among each other.  One GPU stands in for all of them here: the launches of different
+    # ranks go to 4 streams (the hardware queues a process has), rank r on stream r % 4, each
+    # rank's four shards in order.  This is the recorded protocol for configs[1].
     streams = [torch.cuda.Stream(device=dev) for _ in range(4)]
 
-    def quantize_layer_streams():
+    def quantize_layer_rank_streams():
         main = torch.cuda.current_stream(dev)
         for st in streams:
             st.wait_stream(main)
-        for i, (lo, sh) in enumerate(shards):
-            zpp.qwz_quantize(w[lo:lo + sh], B, 8, codes=codes[lo:lo + sh], scales=scales[lo // B:(lo + sh) // B],
-                             stream=streams[i % 4])
+        for lo, sh, rank in shards:
+            quantize_shard(lo, sh, streams[rank % 4])
         for st in streams:
             main.wait_stream(st)
 
-    run("cfg1.qwz_quantize_32_shards_4_streams", Bytes.quantize(n_total, B, 8), quantize_layer_streams,
-        "as above, launches round-robin on 4 streams so that one shard's tail overlaps the next one's start", batch=2)
+    run("cfg1.qwz_quantize_32_shards_rank_streams", nb, quantize_layer_rank_streams,
+        "recorded protocol for configs[1]: the same 32 launches, simulated rank r on stream r % 4 "
+        "(ranks are independent processes in the method), fork and join through events", batch=2, launches=32)
+    # both sequences captured into HIP graphs (kernel nodes only) and replayed
+    cap = torch.cuda.Stream(device=dev)
+    for key, fn in (("cfg1.qwz_quantize_32_shards_graph", quantize_layer),
+                    ("cfg1.qwz_quantize_32_shards_rank_streams_graph", quantize_layer_rank_streams)):
+        g = torch.cuda.CUDAGraph()
+        cap.wait_stream(torch.cuda.current_stream(dev))
+        with torch.cuda.stream(cap):
+            with torch.cuda.graph(g, stream=cap):
+                fn()
+        torch.cuda.current_stream(dev).wait_stream(cap)
+        run(key, nb, g.replay, "the sequence above captured once into a HIP graph and replayed", batch=2, launches=32)
+        del g
     run("cfg1.qwz_dequantize_layer", Bytes.dequantize(n_total, B, 8),
         lambda: zpp.qwz_dequantize(codes, scales, n_total, B, 8, out=w), batch=4)
     del w, codes, scales
@@ -417,7 +530,6 @@ def per_config_kernels(torch, zpp, workloads, dev):
         zpp.qgz_reorder(grads[r], X, Y, 1, B, 4, codes=first[r][0], scales=first[r][1])
 
     run("cfg2.qgz_reorder_per_rank", Bytes.quantize(n, B, 4), reorder_one)
-    del grads
     co = torch.empty(m // 2, dtype=torch.uint8, device=dev)
     so = torch.empty(m // B, dtype=torch.float32, device=dev)
     cb, sb = m // 2, m // B
@@ -431,7 +543,36 @@ def per_config_kernels(torch, zpp, workloads, dev):
         zpp.qgz_intra_reduce(tables[j], None, m, B, 4, codes_out=co, scales_out=so)
 
     run("cfg2.qgz_intra_reduce_per_rank", Bytes.intra(m, B, 4, X), intra_one)
-    del first, co, so, tables
+
+    # the paths that parity tests cover for other block sizes, at the same sizes: a block that is not a
+    # power of two (1536 = 3 x 512) and the int4 intra-node stage with the largest block (4096, two waves
+    # wide).  They are one wave per block, the quantizer reading every block twice (the second time from cache).
+    GBk = 1536
+    ng = n - n % (X * Y * GBk)
+    gq = grads[0][:ng]
+    qc = torch.empty(ng // 2, dtype=torch.uint8, device=dev)
+    qs = torch.empty(ng // GBk, dtype=torch.float32, device=dev)
+    note = "block 1536: the path for blocks that are not powers of two"
+    run("generic.qgz_reorder_block1536", Bytes.quantize(ng, GBk, 4), lambda: zpp.qgz_reorder(gq, X, Y, 1, GBk, 4, codes=qc, scales=qs), note)
+    gy = torch.empty(ng, dtype=torch.float16, device=dev)
+    run("generic.qwz_dequantize_block1536", Bytes.dequantize(ng, GBk, 4), lambda: zpp.qwz_dequantize(qc, qs, ng, GBk, 4, out=gy), note)
+    del gy
+    mg = m - m % GBk
+    for blk, key in ((GBk, "generic.qgz_intra_reduce_block1536"), (4096, "generic.qgz_intra_reduce_block4096")):
+        mm = m - m % blk
+        enc = [zpp.qwz_quantize(grads[k][:mm], blk, 4) for k in range(X)]
+        tb = zpp.PeerTable([e[0] for e in enc], [e[1] for e in enc])
+        run(key, Bytes.intra(mm, blk, 4, X),
+            lambda: zpp.qgz_intra_reduce(tb, None, mm, blk, 4, codes_out=co, scales_out=so),
+            "one wave per block, sums parked in LDS between the maximum and the encode")
+        del enc, tb
+    Lg = 4718592                                            # the step's inter-node size, a multiple of 1536
+    enc = [zpp.qwz_quantize(grads[k % X][(k // X) * Lg:(k // X + 1) * Lg], GBk, 4) for k in range(48)]
+    tb = zpp.PeerTable([e[0] for e in enc], [e[1] for e in enc])
+    og = torch.empty(Lg, dtype=torch.float32, device=dev)
+    run("generic.qgz_inter_reduce_block1536", Bytes.inter(Lg, GBk, 4, 48),
+        lambda: zpp.qgz_inter_reduce(tb, None, Lg, GBk, 4, 384.0, out=og), "every lane fetches its own scales")
+    del enc, tb, og, gq, qc, qs, grads, first, co, so, tables
 
     # configs[3]: 48 node chunks of 46,875,136 elements (46,875,000 padded to the block), int4 block 512
     Y, L = 48, 46875136
@@ -450,8 +591,9 @@ def per_config_kernels(torch, zpp, workloads, dev):
 def cpu_baseline(args, n_L, X, Y, W, WB, WBITS, GB_, GBITS):
     """The CPU oracle, as it stands, on 1/div of one layer pushed through the same
     six calls a layer costs in a step (2 dequantize, reorder, intra, inter, quantize):
-    on all host threads, and on 1/16 of that sample with one thread (whose outputs
-    must be the bytes the threaded run gives for the same sample)."""
+    on all host threads (best of 3, outputs allocated and touched beforehand), and on
+    1/16 of that sample with one thread (whose outputs must be the bytes the threaded
+    run gives for the same sample)."""
     import numpy as np
     import torch
     import oracle
@@ -470,32 +612,43 @@ def cpu_baseline(args, n_L, X, Y, W, WB, WBITS, GB_, GBITS):
         nodes = [oracle.qwz_quantize(workloads.as_bits(workloads.gradients(L, device=gen, tensor_id=200 + i, tail_std=0.0)),
                                      oracle.F16, GB_, GBITS) for i in range(Y - 1)]
         own = workloads.as_bits(workloads.weights(L, device=gen, tensor_id=2))
-        return n, wc, ws, g, peers, nodes, own
+        outs = {"y": np.zeros(n, np.uint16), "gc": np.zeros(n // 2, np.uint8), "gs": np.zeros(n // GB_, np.float32),
+                "ic": np.zeros(m // 2, np.uint8), "is": np.zeros(m // GB_, np.float32), "o": np.zeros(L, np.float32),
+                "qc": np.zeros(L, np.uint8), "qs": np.zeros(L // WB, np.float32)}
+        return n, wc, ws, g, peers, nodes, own, outs
 
     def six(inp):
-        n, wc, ws, g, peers, nodes, own = inp
+        n, wc, ws, g, peers, nodes, own, o = inp
         m, L = n // X, n // W
         t0 = time.perf_counter()
-        y1 = oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
-        oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16)
-        gc, gs = oracle.qgz_reorder(g, oracle.F16, X, Y, 1, GB_, GBITS)
-        ic, isc = oracle.qgz_intra_reduce([gc[:m // 2]] + [p[0] for p in peers], [gs[:m // GB_]] + [p[1] for p in peers],
-                                          m, GB_, GBITS)
-        out = oracle.qgz_inter_reduce([ic[:L // 2]] + [c for c, _ in nodes], [isc[:L // GB_]] + [s for _, s in nodes],
-                                      L, GB_, GBITS, float(W))
-        qc, qs = oracle.qwz_quantize(own, oracle.BF16, WB, WBITS)
+        oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16, out=o["y"])
+        oracle.qwz_dequantize(wc, ws, n, WB, WBITS, oracle.BF16, out=o["y"])
+        oracle.qgz_reorder(g, oracle.F16, X, Y, 1, GB_, GBITS, codes=o["gc"], scales=o["gs"])
+        oracle.qgz_intra_reduce([o["gc"][:m // 2]] + [p[0] for p in peers], [o["gs"][:m // GB_]] + [p[1] for p in peers],
+                                m, GB_, GBITS, codes=o["ic"], scales=o["is"])
+        oracle.qgz_inter_reduce([o["ic"][:L // 2]] + [c for c, _ in nodes], [o["is"][:L // GB_]] + [s for _, s in nodes],
+                                L, GB_, GBITS, float(W), out=o["o"])
+        oracle.qwz_quantize(own, oracle.BF16, WB, WBITS, codes=o["qc"], scales=o["qs"])
         dt = time.perf_counter() - t0
-        nbytes = (2 * Bytes.dequantize(n, WB, WBITS) + Bytes.quantize(n, GB_, GBITS) + Bytes.intra(m, GB_, GBITS, X)
-                  + Bytes.inter(L, GB_, GBITS, Y) + Bytes.quantize(L, WB, WBITS))
-        return dt, nbytes, (y1, gc, gs, ic, isc, out, qc, qs)
+        return dt, six_bytes(n), [v.copy() for v in o.values()]
+
+    def six_bytes(n):
+        m, L = n // X, n // W
+        return (2 * Bytes.dequantize(n, WB, WBITS) + Bytes.quantize(n, GB_, GBITS) + Bytes.intra(m, GB_, GBITS, X)
+                + Bytes.inter(L, GB_, GBITS, Y) + Bytes.quantize(L, WB, WBITS))
 
     div = args.cpu_sample_div
     threads = oracle.set_threads(0)
-    dt, nbytes, _ = six(prepare(n_L // div))
+    inp = prepare(n_L // div)
+    runs = [six(inp)[0] for _ in range(3)]
+    dt = min(runs)
+    nbytes = six_bytes(n_L // div)
     res = {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
            "sample": f"1/{div} of one layer ({n_L // div} elements) through the six calls a layer costs per step "
-                     f"(= 1/{div * args.layers} of a step), {dt:.1f} s of wall time",
+                     f"(= 1/{div * args.layers} of a step); best of 3 runs of {dt:.1f} s "
+                     f"({', '.join(f'{r:.2f}' for r in runs)} s), outputs allocated beforehand",
            "seconds": round(dt, 2)}
+    del inp
     small = prepare(n_L // (16 * div))
     _, _, threaded = six(small)
     oracle.set_threads(1)

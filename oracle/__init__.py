@@ -78,8 +78,13 @@ def codes_nbytes(n, bits):
     return n * bits // 8
 
 
-def _new_codes(n, bits):
-    return np.zeros(codes_nbytes(n, bits), dtype=np.uint8)
+def _out(given, size, dtype, name):
+    """A caller's output array (exact size and type, contiguous) or a new zeroed one."""
+    if given is None:
+        return np.zeros(size, dtype=dtype)
+    if not (isinstance(given, np.ndarray) and given.dtype == dtype and given.size == size and given.flags.c_contiguous):
+        raise TypeError(f"{name}: needs a contiguous {np.dtype(dtype).name} array of {size} elements")
+    return given
 
 
 def set_threads(t):
@@ -87,30 +92,31 @@ def set_threads(t):
     return lib().oracle_set_threads(int(t))
 
 
-def qwz_quantize(x, dtype, block, bits=8):
+def qwz_quantize(x, dtype, block, bits=8, codes=None, scales=None):
+    """codes / scales / out arguments of this module: optional arrays to write the result into."""
     x = _as_input(x, dtype)
     n = x.size
-    codes = _new_codes(n, bits)
-    scales = np.zeros(max(n // max(block, 1), 0), dtype=np.float32)
+    codes = _out(codes, codes_nbytes(n, bits), np.uint8, "codes")
+    scales = _out(scales, max(n // max(block, 1), 0), np.float32, "scales")
     _check(lib().oracle_qwz_quantize(_ptr(x), dtype, n, block, bits, _ptr(codes), _ptr(scales)),
            "qwz_quantize")
     return codes, scales
 
 
-def qwz_dequantize(codes, scales, n, block, bits=8, out_dtype=F16):
+def qwz_dequantize(codes, scales, n, block, bits=8, out_dtype=F16, out=None):
     codes = np.ascontiguousarray(codes).view(np.uint8).reshape(-1)
     scales = np.ascontiguousarray(scales, dtype=np.float32)
-    y = np.zeros(n, dtype=np.float32 if out_dtype == F32 else np.uint16)
+    y = _out(out, n, np.float32 if out_dtype == F32 else np.uint16, "out")
     _check(lib().oracle_qwz_dequantize(_ptr(codes), _ptr(scales), n, block, bits, out_dtype, _ptr(y)),
            "qwz_dequantize")
     return y
 
 
-def qgz_reorder(grad, dtype, X, Y, S, block, bits=4):
+def qgz_reorder(grad, dtype, X, Y, S, block, bits=4, codes=None, scales=None):
     grad = _as_input(grad, dtype)
     n = grad.size
-    codes = _new_codes(n, bits)
-    scales = np.zeros(n // max(block, 1), dtype=np.float32)
+    codes = _out(codes, codes_nbytes(n, bits), np.uint8, "codes")
+    scales = _out(scales, n // max(block, 1), np.float32, "scales")
     _check(lib().oracle_qgz_reorder(_ptr(grad), dtype, n, X, Y, S, block, bits, _ptr(codes), _ptr(scales)),
            "qgz_reorder")
     return codes, scales
@@ -120,22 +126,22 @@ def _ptr_array(arrs):
     return (ctypes.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
 
 
-def qgz_intra_reduce(codes_in, scales_in, m, block, bits=4):
+def qgz_intra_reduce(codes_in, scales_in, m, block, bits=4, codes=None, scales=None):
     codes_in = [np.ascontiguousarray(c).view(np.uint8).reshape(-1) for c in codes_in]
     scales_in = [np.ascontiguousarray(s, dtype=np.float32) for s in scales_in]
     X = len(codes_in)
-    codes = _new_codes(m, bits)
-    scales = np.zeros(m // max(block, 1), dtype=np.float32)
+    codes = _out(codes, codes_nbytes(m, bits), np.uint8, "codes")
+    scales = _out(scales, m // max(block, 1), np.float32, "scales")
     _check(lib().oracle_qgz_intra_reduce(_ptr_array(codes_in), _ptr_array(scales_in), X, m, block, bits,
                                          _ptr(codes), _ptr(scales)), "qgz_intra_reduce")
     return codes, scales
 
 
-def qgz_inter_reduce(codes_in, scales_in, m, block, bits=4, divisor=1.0):
+def qgz_inter_reduce(codes_in, scales_in, m, block, bits=4, divisor=1.0, out=None):
     codes_in = [np.ascontiguousarray(c).view(np.uint8).reshape(-1) for c in codes_in]
     scales_in = [np.ascontiguousarray(s, dtype=np.float32) for s in scales_in]
     Y = len(codes_in)
-    out = np.zeros(m, dtype=np.float32)
+    out = _out(out, m, np.float32, "out")
     _check(lib().oracle_qgz_inter_reduce(_ptr_array(codes_in), _ptr_array(scales_in), Y, m, block, bits,
                                          float(divisor), _ptr(out)), "qgz_inter_reduce")
     return out
