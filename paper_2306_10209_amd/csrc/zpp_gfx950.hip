@@ -12,7 +12,6 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "zpp.h"
 #include "zpp_diagnostics.h"
@@ -339,11 +338,11 @@ __device__ __host__ __forceinline__ uint64_t source_slice32(uint32_t p, uint32_t
 
 // One tile.  FULL: the whole tile lies inside the slice, so no lane is masked;
 // otherwise lanes past the end of the slice are masked.  DEEP = false: a wave waits
-// for each load before it issues the next; with a grid of many residency rounds the
+// for each load before it issues the next; in a launch of very many residency rounds the
 // other waves of the SIMD keep the memory system busy, and more bytes in flight only
-// queue up (-7 % with all of a tile's loads outstanding).  DEEP = true: all of the
-// tile's loads are issued at once; for a launch of one or two rounds the chip is not
-// yet (or no longer) full, and a wave's own latency chain is what the launch lasts.
+// queue up (-3 to -7 % with all of a tile's loads outstanding).  DEEP = true: all of the
+// tile's loads are issued at once; in a shorter launch the chip is not yet (or no longer)
+// full for a good part of it, and a wave's own chain of load latencies is what counts.
 template <int DT, int BITS, int LOG2B, int V, bool FULL, bool DEEP>
 __device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                               float* __restrict__ scales, uint64_t in_base, uint64_t out_base,
@@ -421,9 +420,13 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ 
         quantize_tile<DT, BITS, LOG2B, V, false, DEEP>(x, codes, scales, in_base, out_base, rem, lane);
 }
 
-// Any block size that is a multiple of 32 (not a power of two, or larger than the
-// tiled kernel handles): one wave per block, two passes over the block; the second
-// pass re-reads what the first pulled into cache.
+// Any other block size that is a multiple of 32 (not a power of two): one wave per block.
+// The largest block, 4096 elements, is 8 rounds of 64 lanes x 8 elements, so the whole
+// block waits in registers between the maximum and the encode, as in the tiled kernel: the
+// tensor is read once.  Rounds past the end of the block are skipped (same in every lane);
+// in the last round the lanes past its end are masked.
+constexpr int kBlockRounds = 8;
+
 template <int DT, int BITS>
 __global__ __launch_bounds__(kThreads) void k_quantize_anyblock(const void* __restrict__ x,
                                                                 uint8_t* __restrict__ codes,
@@ -438,20 +441,30 @@ __global__ __launch_bounds__(kThreads) void k_quantize_anyblock(const void* __re
     const uint64_t p = ob / bps, r = ob % bps;
     const uint64_t src = (X == 1 || Y == 1) ? p : source_slice(p, X, Y);
     const uint64_t in_base = src * L + r * B, out_base = ob * B;
-    float a = 0.0f;
-    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
-        float f[8];
-        load8<DT>(x, in_base + off, f);
-        a = fmaxf(a, absmax8(f));
+    const uint32_t chunks = B / 8;  // 8-element pieces of the block
+    float f[kBlockRounds][8];
+#pragma unroll
+    for (int k = 0; k < kBlockRounds; ++k) {
+        const uint32_t c = (uint32_t)k * kWave + lane;
+        if ((uint32_t)k * kWave < chunks && c < chunks) {
+            load8<DT>(x, in_base + c * 8u, f[k]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) f[k][i] = 0.0f;
+        }
     }
+    float a = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kBlockRounds; ++k)
+        if ((uint32_t)k * kWave < chunks) a = fmaxf(a, absmax8(f[k]));
     a = group_max<kWave>(a);
     float scale, inv;
     block_scale<BITS>(a, scale, inv);
     if (lane == 0) scales[ob] = scale;
-    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
-        float f[8];
-        load8<DT>(x, in_base + off, f);
-        store_codes8<BITS>(codes, out_base + off, f, inv);
+#pragma unroll
+    for (int k = 0; k < kBlockRounds; ++k) {
+        const uint32_t c = (uint32_t)k * kWave + lane;
+        if ((uint32_t)k * kWave < chunks && c < chunks) store_codes8<BITS>(codes, out_base + c * 8u, f[k], inv);
     }
 }
 
@@ -1043,51 +1056,58 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
     }
 }
 
-// qgz_intra_reduce for any other block size: one wave per block, the sums wait in
-// LDS between the maximum and the encode.
+// qgz_intra_reduce for any other block size (not a power of two, or wider than a wave of
+// 16-byte vectors): one wave per block, 8 elements per lane and round, at most 8 rounds.  The
+// sums of the whole block wait in registers between the maximum and the encode.  The peers
+// are the outer loop: per peer one scale (the same for the whole wave) and one load per
+// round, all issued before the first decode.
 template <int BITS>
-__global__ __launch_bounds__(kWave) void k_intra_reduce_anyblock(const PeerTable P, int K, uint32_t B,
-                                                                 uint8_t* __restrict__ codes_out,
-                                                                 float* __restrict__ scales_out)
+__global__ __launch_bounds__(kThreads) void k_intra_reduce_anyblock(const PeerTable P, int K, uint32_t B,
+                                                                    uint64_t blocks,
+                                                                    uint8_t* __restrict__ codes_out,
+                                                                    float* __restrict__ scales_out)
 {
-    __shared__ float sums[4096];
-    const int lane = threadIdx.x;
-    const uint64_t blk = blockIdx.x;
-    const uint64_t base = blk * B;
-    float a = 0.0f;
-    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
-        float r[8];
+    constexpr int NW = BITS == 4 ? 1 : 2;  // code dwords of 8 elements
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t blk = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (blk >= blocks) return;
+    const uint32_t chunks = B / 8;  // 8-element pieces of the block
+    const uint64_t base_byte = blk * B * BITS / 8;
+    uint32_t off[kBlockRounds];  // byte offset of the lane's piece in each round (lanes past the end repeat piece 0)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r[i] = 0.0f;
-        const uint64_t e = base + off;
-        for (int k = 0; k < K; ++k) {
-            const float s = P.scales[k][blk];
-            if (BITS == 4) {
-                const uint32_t w = *reinterpret_cast<const uint32_t*>(P.codes[k] + (e >> 1));
+    for (int r = 0; r < kBlockRounds; ++r) {
+        const uint32_t c = (uint32_t)r * kWave + lane;
+        off[r] = (c < chunks ? c : 0u) * (uint32_t)BITS;
+    }
+    float acc[kBlockRounds][8];
+    for (int k = 0; k < K; ++k) {
+        const float s = P.scales[k][blk];
+        const uint8_t* src = P.codes[k] + base_byte;
+        uint32_t w[kBlockRounds][NW];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) r[i] = r[i] + nibble_f32(w, i) * s;
-            } else {
-                const u32x2 w = *reinterpret_cast<const u32x2*>(P.codes[k] + e);
+        for (int r = 0; r < kBlockRounds; ++r)
+            if ((uint32_t)r * kWave < chunks) load_words<NW>(src + off[r], w[r]);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    r[i] = r[i] + byte_f32(w.x, i) * s;
-                    r[4 + i] = r[4 + i] + byte_f32(w.y, i) * s;
-                }
+        for (int r = 0; r < kBlockRounds; ++r)
+            if ((uint32_t)r * kWave < chunks) {
+                if (k == 0) accumulate<BITS, NW, true>(acc[r], w[r], s);
+                else accumulate<BITS, NW, false>(acc[r], w[r], s);
             }
-        }
+    }
+    float a = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) sums[off + i] = r[i];
-        a = fmaxf(a, absmax8(r));
+    for (int r = 0; r < kBlockRounds; ++r) {
+        const uint32_t c = (uint32_t)r * kWave + lane;
+        if ((uint32_t)r * kWave < chunks && c < chunks) a = fmaxf(a, absmax8(acc[r]));
     }
     a = group_max<kWave>(a);
     float scale, inv;
     block_scale<BITS>(a, scale, inv);
     if (lane == 0) scales_out[blk] = scale;
-    for (uint32_t off = lane * 8u; off < B; off += kWave * 8u) {
-        float r[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r[i] = sums[off + i];  // written by this same lane
-        store_codes8<BITS>(codes_out, base + off, r, inv);
+    for (int r = 0; r < kBlockRounds; ++r) {
+        const uint32_t c = (uint32_t)r * kWave + lane;
+        if ((uint32_t)r * kWave < chunks && c < chunks) store_codes8<BITS>(codes_out, blk * B + c * 8u, acc[r], inv);
     }
 }
 
@@ -1266,24 +1286,10 @@ constexpr uint64_t kMaxGrid = 0x7fffffffull;
 // wave slots of the chip at full occupancy: 256 CUs x 4 SIMDs x 8 waves
 constexpr uint64_t kWaveSlots = 256ull * 4 * 8;
 
-#ifdef ZPP_DEV_TUNE
-// development builds only: integer overrides from the environment for tuning sweeps
-long dev_tune(const char* name, long dflt)
-{
-    const char* v = getenv(name);
-    return v ? atol(v) : dflt;
-}
-#endif
-
-// quantize launches of at most this many wave tiles issue all of a tile's loads at once
-uint64_t deep_tiles_limit()
-{
-#ifdef ZPP_DEV_TUNE
-    return (uint64_t)dev_tune("ZPP_DEEP_TILES", 2 * kWaveSlots);
-#else
-    return 2 * kWaveSlots;
-#endif
-}
+// Quantize launches of at most this many wave tiles (16 residency rounds) issue all of a tile's
+// loads at once.  Measured over 2^23 .. 2^29 elements: with four loads per tile that is 3 to 14 %
+// faster up to about this size, the same at twice the size and 3 % slower beyond.
+constexpr uint64_t kDeepTilesLimit = 16 * kWaveSlots;
 
 template <int DT, int BITS, int LOG2B>
 int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t L, uint64_t slices, uint32_t X,
@@ -1297,7 +1303,7 @@ int launch_quantize_tiled(const void* x, uint8_t* codes, float* scales, uint64_t
     const uint64_t grid = plan_grid((tiles + kWavesPerWG - 1) / kWavesPerWG, xcd_shift);
     if (grid > kMaxGrid || tiles >= (1ull << 32) || slices >= (1ull << 32)) return ZPP_EINVAL;
     const FastDiv by_tps = make_fastdiv((uint32_t)tps), byT = make_fastdiv(X * Y), byY = make_fastdiv(Y);
-    if (tiles <= deep_tiles_limit())
+    if (tiles <= kDeepTilesLimit)
         k_quantize<DT, BITS, LOG2B, V, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
             x, codes, scales, L, by_tps, (uint32_t)tiles, X, byT, byY, xcd_shift);
     else
@@ -1377,7 +1383,8 @@ int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* cod
     default: break;
     }
 #undef ZPP_I
-    k_intra_reduce_anyblock<BITS><<<dim3((uint32_t)(m / B)), dim3(kWave), 0, st>>>(P, K, B, codes_out, scales_out);
+    const uint64_t blocks = m / B, groups = (blocks + kWavesPerWG - 1) / kWavesPerWG;
+    k_intra_reduce_anyblock<BITS><<<dim3((uint32_t)groups), dim3(kThreads), 0, st>>>(P, K, B, blocks, codes_out, scales_out);
     return launch_status();
 }
 
@@ -1452,11 +1459,7 @@ int launch_inter(const PeerTable& P, int K, uint64_t m, uint32_t B, const Diviso
     constexpr uint32_t E = EPL<BITS, 1>::value;
     const int l2 = log2_or_neg(B);
     if (l2 >= 0 && B >= 16 * E) {  // a row of 16 lanes inside one block: the row form
-        int c = inter_rows_vectors((m + kWave * E - 1) / (kWave * E));
-#ifdef ZPP_DEV_TUNE
-        const int fc = (int)dev_tune("ZPP_INTER_C", 0);
-        if (fc >= 1 && fc <= 3) c = fc;
-#endif
+        const int c = inter_rows_vectors((m + kWave * E - 1) / (kWave * E));
         // peers per fetch group: 8 where a wave has one vector (more bytes in flight per wave), 4 otherwise
         if (c == 1) return launch_inter_rows<BITS, 1, 8>(P, K, m, l2, dv, out, st);
         if (c == 2) return launch_inter_rows<BITS, 2, 4>(P, K, m, l2, dv, out, st);
