@@ -188,22 +188,34 @@ def main():
     events = {k: [] for k in bytes_per}
     DOM = "qwz_dequantize"
     counter = [0]
+    last = [None]
 
     def timed(name, l, record):
-        """record: "all" brackets every launch with HIP events; "sparse" only every fourth launch
-        of the dominant kernel (an event pair costs a few microseconds of queue time, and the
-        timed region should pay as little of that as possible)."""
+        """record = "sparse": every fourth launch of the dominant kernel sits between two HIP events of
+        its own (an event costs a few microseconds of queue time, and the timed region should pay
+        as little of that as possible).  record = "all": one event after every launch; a kernel's
+        time runs from the event after the launch before it to the event after its own, the
+        accounting rocprofv3's kernel trace uses for back-to-back launches on one queue."""
         counter[0] += 1
-        if record == "all" or (record == "sparse" and name == DOM and counter[0] % 4 == 0):
+        if record == "sparse" and name == DOM and counter[0] % 4 == 0:
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             launch[name](l)
             b.record()
             events[name].append((a, b))
+        elif record == "all":
+            launch[name](l)
+            b = torch.cuda.Event(enable_timing=True)
+            b.record()
+            events[name].append((last[0], b))
+            last[0] = b
         else:
             launch[name](l)
 
     def step(record):
+        if record == "all":
+            last[0] = torch.cuda.Event(enable_timing=True)
+            last[0].record()
         for l in range(layers):                                   # forward
             timed("qwz_dequantize", l, record)
         for l in reversed(range(layers)):                         # backward
@@ -236,7 +248,8 @@ def main():
         gbs = bytes_per[k] / (avg * 1e-3) / 1e9
         kernels[k] = {"bytes": bytes_per[k], "avg_ms": round(avg, 5), "min_ms": round(min(ms), 5),
                       "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                      "launches": len(ms), "protocol": "one launch between two HIP events, inside the step"}
+                      "launches": len(ms),
+                      "protocol": "inside the step, one HIP event after every launch; from the event before to the event after"}
         # vector-ALU instructions per launch from a committed rocprofv3 --pmc SQ_INSTS_VALU summary: one
         # wave64 instruction is 64 lane-operations; the chip retires 256 CUs x 4 SIMDs x 16 lanes x
         # 2.4 GHz = 39.3e12 of them per second at its peak clock

@@ -28,12 +28,33 @@ def test_blocked_error_shrinks_with_the_block_and_beats_one_scale():
     assert whole / errs[2] > 2.0            # block 2048 on these weights: several times smaller error
 
 
+def test_one_scale_baseline_by_padding_equals_its_definition():
+    """The study gets "one scale for the whole tensor" from the block quantizer by padding every
+    block with the tensor's largest element.  On the oracle: that is the plain definition
+    (scale = absmax / 127 for the whole tensor, round half to even), element by element."""
+    from paper_2306_10209_amd import error_study
+    w = workloads.weights(4064 * 50, seed=23)
+    padded, kept = error_study.whole_tensor_layout(w)
+    c, s = oracle.qwz_quantize(workloads.as_bits(padded), oracle.BF16, 4096, 8)
+    codes = oracle.unpack_codes(c, padded.numel(), 8).reshape(-1, 4096)[:, :4064].reshape(-1)
+    x = kept.float().numpy()
+    a = np.float32(np.max(np.abs(x)))
+    assert np.all(s == np.float32(a / np.float32(127.0)))
+    want = np.rint(x * np.float32(np.float32(127.0) / a)).astype(np.int32)
+    assert np.array_equal(codes, want)
+
+
 @pytest.mark.gpu
 def test_library_study_matches_oracle_numbers():
     from paper_2306_10209_amd import error_study
-    n = 1 << 20
+    n = 4064 * 256
     w = workloads.weights(n, seed=17)
     x32 = w.float().numpy().astype(np.float64)
-    rows = error_study.study(w.to("cuda:0"), blocks=(64, 2048), bits=8)
-    for b in (64, 2048):
+    rows = error_study.study(w.to("cuda:0"), blocks=(32, 4064), bits=8)
+    for b in (32, 4064):
         assert abs(rows["blocks"][b]["rms"] - oracle_rms(workloads.as_bits(w), x32, b, 8)) < 1e-12
+    padded, kept = error_study.whole_tensor_layout(w)
+    c, s = oracle.qwz_quantize(workloads.as_bits(padded), oracle.BF16, 4096, 8)
+    y = oracle.qwz_dequantize(c, s, padded.size(0), 4096, 8, oracle.F32).reshape(-1, 4096)[:, :4064].reshape(-1)
+    whole = float(np.sqrt(np.mean((y.astype(np.float64) - kept.float().numpy().astype(np.float64)) ** 2)))
+    assert abs(rows["unblocked_rms"] - whole) < 1e-12
