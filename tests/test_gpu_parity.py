@@ -544,18 +544,34 @@ def test_short_division_equals_division_for_every_dividend(divisor):
     assert diagnostics.selfcheck_divide(divisor) == 0
 
 
-@pytest.mark.parametrize("Y,blocks,div", [(48, 9216 // 8, 384.0), (48, 12288 // 8 + 3, 384.0), (9, 8192 // 8 + 1, 3.0),
-                                          (17, 1537, 17.0), (4, 2049, 4.0), (64, 1031, 0.37)])
+@pytest.mark.parametrize("Y,blocks,div", [(48, 1152, 384.0), (5, 8192, 5.0), (4, 8193, 384.0), (3, 9215, 3.0),
+                                          (6, 9216, 384.0), (3, 10241, 7.0), (4, 12288, 4.0), (3, 12289, 0.37),
+                                          (17, 1537, 17.0), (64, 1031, 1e-5)])
 def test_qgz_inter_reduce_across_launch_shapes(Y, blocks, div):
     """Sizes on both sides of the limits at which the launch changes the number of vectors a
-    wave takes (one, two or three; the ragged last wave then ends inside a wave's tile), with
-    divisors that take the short division, the reciprocal multiply and the plain division."""
+    wave takes: one up to 8192 wave tiles and above 12288, two or three in between (9216 tiles
+    is the benchmark step's launch); odd counts end inside a wave's tile.  The divisors take the
+    short division, the reciprocal multiply (powers of two) and the plain division (1e-5)."""
     block, bits = 512, 4
     m = block * blocks
     host, dev = _peer_inputs(Y, m, block, bits, seed=Y + blocks)
     want = oracle.qgz_inter_reduce([h[0] for h in host], [h[1] for h in host], m, block, bits, div)
     ofull, out = guarded(m, torch.float32)
     zpp.qgz_inter_reduce([d[0] for d in dev], [d[1] for d in dev], m, block, bits, div, out=out)
+    torch.cuda.synchronize()
+    assert eq_bytes(out, want)
+    assert_guards_intact(ofull, m, torch.float32)
+
+
+@pytest.mark.parametrize("tiles", [9216, 10241, 12289])
+def test_qgz_inter_reduce_int8_across_launch_shapes(tiles):
+    """The same launch shapes for int8 codes (a wave tile is 256 elements there)."""
+    block, bits, Y = 256, 8, 3
+    m = 256 * tiles
+    host, dev = _peer_inputs(Y, m, block, bits, seed=tiles)
+    want = oracle.qgz_inter_reduce([h[0] for h in host], [h[1] for h in host], m, block, bits, 24.0)
+    ofull, out = guarded(m, torch.float32)
+    zpp.qgz_inter_reduce([d[0] for d in dev], [d[1] for d in dev], m, block, bits, 24.0, out=out)
     torch.cuda.synchronize()
     assert eq_bytes(out, want)
     assert_guards_intact(ofull, m, torch.float32)
