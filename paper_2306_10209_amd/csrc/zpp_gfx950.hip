@@ -1432,12 +1432,12 @@ int launch_inter_rows(const PeerTable& P, int K, uint64_t m, int l2, const Divis
 // same number of tiles and that they all start together: a launch that does not fill more
 // than a few residency rounds is cut into waves of C tiles such that all waves are resident
 // at once (one round, no second round that runs nearly empty), choosing the C that leaves
-// the fewest idle tile slots.  Resident waves per SIMD by registers and LDS: 8, 6, 4 for
+// the fewest idle tile slots.  Resident waves per SIMD by registers and LDS: 8, 5, 4 for
 // C = 1, 2, 3.  Larger launches take C = 1 and let the dispatcher balance.
 int inter_rows_vectors(uint64_t tiles)
 {
     constexpr uint64_t simds = 256 * 4;
-    constexpr uint64_t resident[4] = {0, 8, 6, 4};
+    constexpr uint64_t resident[4] = {0, 8, 5, 4};
     if (tiles <= resident[1] * simds || tiles > 3 * resident[3] * simds) return 1;
     int best = 1;
     uint64_t best_cost = ~0ull;

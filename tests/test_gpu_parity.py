@@ -545,7 +545,7 @@ def test_short_division_equals_division_for_every_dividend(divisor):
 
 
 @pytest.mark.parametrize("Y,blocks,div", [(48, 1152, 384.0), (5, 8192, 5.0), (4, 8193, 384.0), (3, 9215, 3.0),
-                                          (6, 9216, 384.0), (3, 10241, 7.0), (4, 12288, 4.0), (3, 12289, 0.37),
+                                          (6, 9216, 384.0), (3, 10239, 7.0), (3, 10240, 3.0), (3, 10241, 7.0), (4, 12288, 4.0), (3, 12289, 0.37),
                                           (17, 1537, 17.0), (64, 1031, 1e-5)])
 def test_qgz_inter_reduce_across_launch_shapes(Y, blocks, div):
     """Sizes on both sides of the limits at which the launch changes the number of vectors a
@@ -563,7 +563,7 @@ def test_qgz_inter_reduce_across_launch_shapes(Y, blocks, div):
     assert_guards_intact(ofull, m, torch.float32)
 
 
-@pytest.mark.parametrize("tiles", [9216, 10241, 12289])
+@pytest.mark.parametrize("tiles", [9216, 10240, 12289])
 def test_qgz_inter_reduce_int8_across_launch_shapes(tiles):
     """The same launch shapes for int8 codes (a wave tile is 256 elements there)."""
     block, bits, Y = 256, 8, 3
