@@ -768,7 +768,7 @@ __device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, ui
 }
 
 // ---------------------------------------------------------------------------
-// reduce stages, row form: power-of-two blocks of at least 16 lanes x E elements
+// qgz_inter_reduce, row form: power-of-two blocks of at least 16 lanes x E elements
 // ---------------------------------------------------------------------------
 //
 // A lane takes, per peer, C vectors of NW code dwords (E = NW * 32 / BITS elements each);
@@ -780,7 +780,9 @@ __device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, ui
 // all peers), derives the operands of the int4 decode for them and parks them in a table
 // of the wave; each peer's operands are then read back with one broadcast LDS read per
 // row.  That takes the scale load, its address arithmetic and the three multiplies per
-// peer and lane off the vector ALU, which is what bounds these kernels.
+// peer and lane off the vector ALU, which is what bounds this kernel.  (The intra-node stage
+// keeps per-lane scales: with its 16-byte code vectors they are 5 of the 87 vector instructions
+// a peer costs, less than a table's set-up.)
 //
 // Codes are fetched in groups of U peers into two register sets, the next group's loads
 // issued before the current group is decoded; every branch of the steady state leaves
@@ -880,9 +882,10 @@ __device__ __forceinline__ void load_group_rows(const PeerTable& P, int k0, uint
     }
 }
 
-// Adds peers k0 .. k0 + count - 1 (count <= U; PARTIAL = false: count == U) from w.
+// Adds peers k0 .. k0 + count - 1 (count <= U; PARTIAL = false: count == U) from w to sums
+// that the first group has started.
 // row_tab: the wave's table advanced to this lane's row.
-template <int BITS, int NW, int C, int U, bool FIRST, bool PARTIAL>
+template <int BITS, int NW, int C, int U, bool PARTIAL>
 __device__ __forceinline__ void add_group_rows(float (&acc)[C][(EPL<BITS, NW>::value)], const uint32_t (&w)[U][C][NW],
                                                const float* __restrict__ row_tab, int k0, int count)
 {
@@ -900,13 +903,9 @@ __device__ __forceinline__ void add_group_rows(float (&acc)[C][(EPL<BITS, NW>::v
                 op.hi = tc[1];
                 op.bias = tc[2];
 #pragma unroll
-                for (int j = 0; j < NW; ++j) {
-                    if (FIRST && u == 0) add_nibbles8<true>(acc[c] + j * 8, w[u][c][j], op);
-                    else add_nibbles8<false>(acc[c] + j * 8, w[u][c][j], op);
-                }
+                for (int j = 0; j < NW; ++j) add_nibbles8<false>(acc[c] + j * 8, w[u][c][j], op);
             } else {
-                if (FIRST && u == 0) accumulate_plain<BITS, NW, true>(acc[c], w[u][c], tc[0]);
-                else accumulate_plain<BITS, NW, false>(acc[c], w[u][c], tc[0]);
+                accumulate_plain<BITS, NW, false>(acc[c], w[u][c], tc[0]);
             }
         }
     }
@@ -960,18 +959,18 @@ __device__ __forceinline__ bool reduce_rows(const PeerTable& P, int K, uint64_t 
     const float* row_tab = tab + (lane >> 4) * RowTable<BITS, C>::row_pitch;
     for (int g = 1;;) {  // group g is in flight towards wb, wa is free
         if (g + 1 >= n) {
-            add_group_rows<BITS, NW, C, U, false, true>(acc, wb, row_tab, g * U, K - g * U);
+            add_group_rows<BITS, NW, C, U, true>(acc, wb, row_tab, g * U, K - g * U);
             break;
         }
         load_group_rows<NW, C, U>(P, (g + 1) * U, tile_byte, lane_byte, wa);
-        add_group_rows<BITS, NW, C, U, false, false>(acc, wb, row_tab, g * U, U);
+        add_group_rows<BITS, NW, C, U, false>(acc, wb, row_tab, g * U, U);
         ++g;  // group g is in flight towards wa, wb is free
         if (g + 1 >= n) {
-            add_group_rows<BITS, NW, C, U, false, true>(acc, wa, row_tab, g * U, K - g * U);
+            add_group_rows<BITS, NW, C, U, true>(acc, wa, row_tab, g * U, K - g * U);
             break;
         }
         load_group_rows<NW, C, U>(P, (g + 1) * U, tile_byte, lane_byte, wb);
-        add_group_rows<BITS, NW, C, U, false, false>(acc, wa, row_tab, g * U, U);
+        add_group_rows<BITS, NW, C, U, false>(acc, wa, row_tab, g * U, U);
         ++g;
     }
     return facts.mid;
