@@ -73,6 +73,10 @@ QWZ_CASES = [
     (oracle.F32, 4, 2048, 9),
     (oracle.F16, 8, 2048, 1),
     (oracle.F16, 4, 32, 1),
+    (oracle.BF16, 8, 4064, 19),       # one wave per block, 8 rounds, the last one 60 lanes wide
+    (oracle.F16, 4, 2080, 23),        # 5 rounds, the last one 4 lanes wide
+    (oracle.F32, 8, 1056, 11),
+    (oracle.F16, 4, 4032, 5),
 ]
 
 
@@ -271,6 +275,11 @@ INTRA_CASES = [
     (7, 2048, 8, 2),
     (1, 256, 4, 11),
     (64, 128, 4, 5),
+    (8, 4064, 4, 9),      # one wave per block: 8 rounds, ragged last round
+    (5, 2080, 4, 7),
+    (8, 2048, 8, 5),      # int8: wider than a wave of 16-byte vectors
+    (3, 4096, 8, 3),
+    (6, 1056, 8, 13),
 ]
 
 
@@ -546,7 +555,8 @@ def test_short_division_equals_division_for_every_dividend(divisor):
 
 @pytest.mark.parametrize("Y,blocks,div", [(48, 1152, 384.0), (5, 8192, 5.0), (4, 8193, 384.0), (3, 9215, 3.0),
                                           (6, 9216, 384.0), (3, 10239, 7.0), (3, 10240, 3.0), (3, 10241, 7.0), (4, 12288, 4.0), (3, 12289, 0.37),
-                                          (17, 1537, 17.0), (64, 1031, 1e-5)])
+                                          (17, 1537, 17.0), (64, 1031, 1e-5), (1, 9216, 384.0), (2, 9216, 3.0), (64, 9216, 64.0),
+                                          (1, 10240, 5.0)])
 def test_qgz_inter_reduce_across_launch_shapes(Y, blocks, div):
     """Sizes on both sides of the limits at which the launch changes the number of vectors a
     wave takes: one up to 8192 wave tiles and above 12288, two or three in between (9216 tiles
@@ -577,10 +587,12 @@ def test_qgz_inter_reduce_int8_across_launch_shapes(tiles):
     assert_guards_intact(ofull, m, torch.float32)
 
 
-def test_qgz_inter_reduce_with_scales_outside_the_short_division_range():
-    """Tiny (2^-40) and subnormal scales, and huge ones (2^70), keep the plain division; the
-    result is the oracle's bit for bit."""
-    block, bits, blocks, Y = 512, 4, 40, 6
+@pytest.mark.parametrize("blocks,huge", [(40, 2.0 ** 70), (9216, 2.0 ** 70), (9216, 2.0 ** 101), (10240, 2.0 ** 120)])
+def test_qgz_inter_reduce_with_scales_outside_the_short_division_range(blocks, huge):
+    """Tiny (2^-40) and subnormal scales, and huge ones, keep the plain division; scales of
+    2^100 and more also leave the exact int4 decode (every lane then decodes with its own scale
+    loads), at one and at several vectors per wave.  The result is the oracle's bit for bit."""
+    block, bits, Y = 512, 4, 6
     m = block * blocks
     rng = np.random.default_rng(7)
     codes = [rng.integers(0, 256, size=m // 2, dtype=np.uint8) for _ in range(Y)]
@@ -589,7 +601,8 @@ def test_qgz_inter_reduce_with_scales_outside_the_short_division_range():
         s = (10.0 ** rng.uniform(-4, 0, size=blocks)).astype(np.float32)
         s[3 * k % blocks] = np.float32(2.0 ** -40)
         s[(3 * k + 1) % blocks] = np.float32(1e-41)          # subnormal
-        s[(3 * k + 2) % blocks] = np.float32(2.0 ** 70)
+        s[(3 * k + 2) % blocks] = np.float32(huge)
+        s[(977 * k + 5) % blocks] = np.float32(-huge)
         scales.append(s)
     want = oracle.qgz_inter_reduce(codes, scales, m, block, bits, 384.0)
     got = zpp.qgz_inter_reduce([torch.from_numpy(c).to(DEV) for c in codes], [torch.from_numpy(s).to(DEV) for s in scales],
