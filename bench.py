@@ -558,8 +558,8 @@ def per_config_kernels(torch, zpp, workloads, dev, runner):
     run("cfg2.qgz_intra_reduce_per_rank", Bytes.intra(m, B, 4, X), intra_one)
 
     # the paths that parity tests cover for other block sizes, at the same sizes: a block that is not a
-    # power of two (1536 = 3 x 512) and the int4 intra-node stage with the largest block (4096, two waves
-    # wide).  They are one wave per block, the quantizer reading every block twice (the second time from cache).
+    # power of two (1536 = 3 x 512), the int4 intra-node stage with the largest block (4096), and the
+    # inter-node stage with a block that is not a whole number of 16-lane rows (96)
     GBk = 1536
     ng = n - n % (X * Y * GBk)
     gq = grads[0][:ng]
@@ -577,14 +577,20 @@ def per_config_kernels(torch, zpp, workloads, dev, runner):
         tb = zpp.PeerTable([e[0] for e in enc], [e[1] for e in enc])
         run(key, Bytes.intra(mm, blk, 4, X),
             lambda: zpp.qgz_intra_reduce(tb, None, mm, blk, 4, codes_out=co, scales_out=so),
-            "one wave per block, sums parked in LDS between the maximum and the encode")
+            "one wave per block, its sums in registers between the maximum and the encode")
         del enc, tb
     Lg = 4718592                                            # the step's inter-node size, a multiple of 1536
     enc = [zpp.qwz_quantize(grads[k % X][(k // X) * Lg:(k // X + 1) * Lg], GBk, 4) for k in range(48)]
     tb = zpp.PeerTable([e[0] for e in enc], [e[1] for e in enc])
     og = torch.empty(Lg, dtype=torch.float32, device=dev)
     run("generic.qgz_inter_reduce_block1536", Bytes.inter(Lg, GBk, 4, 48),
-        lambda: zpp.qgz_inter_reduce(tb, None, Lg, GBk, 4, 384.0, out=og), "every lane fetches its own scales")
+        lambda: zpp.qgz_inter_reduce(tb, None, Lg, GBk, 4, 384.0, out=og),
+        "12 rows of 16 lanes per block: the kernel of the power-of-two blocks, block index by a prepared division")
+    del enc, tb
+    enc = [zpp.qwz_quantize(grads[k % X][(k // X) * Lg:(k // X + 1) * Lg], 96, 4) for k in range(48)]
+    tb = zpp.PeerTable([e[0] for e in enc], [e[1] for e in enc])
+    run("generic.qgz_inter_reduce_block96", Bytes.inter(Lg, 96, 4, 48),
+        lambda: zpp.qgz_inter_reduce(tb, None, Lg, 96, 4, 384.0, out=og), "every lane fetches its own scales")
     del enc, tb, og, gq, qc, qs, grads, first, co, so, tables
 
     # configs[3]: 48 node chunks of 46,875,136 elements (46,875,000 padded to the block), int4 block 512.

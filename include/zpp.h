@@ -32,6 +32,8 @@
  *     granularities are 16 B aligned).  Tensor lengths must be multiples of the
  *     block; padding is the caller's job.
  *   - Inputs must be finite.  NaN/Inf give unspecified codes (never a fault).
+ *   - Sizes: every call accepts up to 2^31 - 1 blocks; beyond that a call may
+ *     return ZPP_EINVAL (nothing is launched).
  *
  * Arithmetic (fp32, each operation rounded to nearest-even on its own, no fused
  * multiply-add; results are bit-identical to a plain CPU evaluation of these

@@ -423,28 +423,33 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ 
 // Any other block size that is a multiple of 32 (not a power of two): one wave per block.
 // The largest block, 4096 elements, is 8 rounds of 64 lanes x 8 elements, so the whole
 // block waits in registers between the maximum and the encode, as in the tiled kernel: the
-// tensor is read once.  Rounds past the end of the block are skipped (same in every lane);
-// in the last round the lanes past its end are masked.
+// tensor is read once.  R = 2, 4 or 8 rounds are compiled (fewer registers for smaller
+// blocks, so more waves in flight); rounds past the end of the block are skipped (same in
+// every lane), in the last round the lanes past its end are masked.
+// There are fewer than 2^32 blocks in all (the host refuses more), so the wave maps its block to
+// (slice, block in slice) and the slice to its source with the prepared 32-bit divisions.
 constexpr int kBlockRounds = 8;
 
-template <int DT, int BITS>
+template <int DT, int BITS, int R>
 __global__ __launch_bounds__(kThreads) void k_quantize_anyblock(const void* __restrict__ x,
                                                                 uint8_t* __restrict__ codes,
                                                                 float* __restrict__ scales, uint64_t L,
                                                                 uint32_t B, uint64_t total_blocks, uint32_t X,
-                                                                uint32_t Y)
+                                                                uint32_t Y, FastDiv by_blocks_per_slice, FastDiv byT,
+                                                                FastDiv byY)
 {
+    static_assert(R <= kBlockRounds, "a block is at most 8 rounds");
     const int lane = threadIdx.x & (kWave - 1);
     const uint64_t ob = (uint64_t)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (ob >= total_blocks) return;
-    const uint64_t bps = L / B;
-    const uint64_t p = ob / bps, r = ob % bps;
-    const uint64_t src = (X == 1 || Y == 1) ? p : source_slice(p, X, Y);
-    const uint64_t in_base = src * L + r * B, out_base = ob * B;
+    const uint32_t p = fast_div((uint32_t)ob, by_blocks_per_slice);
+    const uint32_t r = (uint32_t)ob - p * by_blocks_per_slice.d;
+    const uint64_t src = (X == 1 || Y == 1) ? (uint64_t)p : source_slice32(p, X, byT, byY);
+    const uint64_t in_base = src * L + (uint64_t)r * B, out_base = ob * B;
     const uint32_t chunks = B / 8;  // 8-element pieces of the block
-    float f[kBlockRounds][8];
+    float f[R][8];
 #pragma unroll
-    for (int k = 0; k < kBlockRounds; ++k) {
+    for (int k = 0; k < R; ++k) {
         const uint32_t c = (uint32_t)k * kWave + lane;
         if ((uint32_t)k * kWave < chunks && c < chunks) {
             load8<DT>(x, in_base + c * 8u, f[k]);
@@ -455,14 +460,14 @@ __global__ __launch_bounds__(kThreads) void k_quantize_anyblock(const void* __re
     }
     float a = 0.0f;
 #pragma unroll
-    for (int k = 0; k < kBlockRounds; ++k)
+    for (int k = 0; k < R; ++k)
         if ((uint32_t)k * kWave < chunks) a = fmaxf(a, absmax8(f[k]));
     a = group_max<kWave>(a);
     float scale, inv;
     block_scale<BITS>(a, scale, inv);
     if (lane == 0) scales[ob] = scale;
 #pragma unroll
-    for (int k = 0; k < kBlockRounds; ++k) {
+    for (int k = 0; k < R; ++k) {
         const uint32_t c = (uint32_t)k * kWave + lane;
         if ((uint32_t)k * kWave < chunks && c < chunks) store_codes8<BITS>(codes, out_base + c * 8u, f[k], inv);
     }
@@ -768,7 +773,7 @@ __device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, ui
 }
 
 // ---------------------------------------------------------------------------
-// qgz_inter_reduce, row form: power-of-two blocks of at least 16 lanes x E elements
+// qgz_inter_reduce, row form: blocks that are a whole number of rows of 16 lanes x E elements
 // ---------------------------------------------------------------------------
 //
 // A lane takes, per peer, C vectors of NW code dwords (E = NW * 32 / BITS elements each);
@@ -980,13 +985,17 @@ __device__ __forceinline__ bool reduce_rows(const PeerTable& P, int K, uint64_t 
 // m is a multiple of the block and the block of 16 * E, so a row of 16 lanes is inside the
 // tensor or outside it as a whole.  Rows outside repeat the addresses of the tile's first
 // row (always inside): they load valid data and store nothing.
-template <int BITS, int NW, int C>
+//
+// POW2: the block is 2^log2b elements.  Otherwise it is rows_per_block.d rows of 16 * E elements
+// and the tensor has fewer than 2^32 rows, so the block index is a 32-bit division of the row
+// index by a divisor prepared on the host.
+template <int BITS, int NW, int C, bool POW2>
 struct RowGeometry {
     static constexpr int E = EPL<BITS, NW>::value;
     bool ok[C];
     uint32_t lane_byte[C];
     uint64_t elem[C], blk[C];
-    __device__ __forceinline__ RowGeometry(uint64_t tile, uint64_t m, int log2b, int lane)
+    __device__ __forceinline__ RowGeometry(uint64_t tile, uint64_t m, int log2b, const FastDiv& rows_per_block, int lane)
     {
 #pragma unroll
         for (int c = 0; c < C; ++c) {
@@ -995,7 +1004,7 @@ struct RowGeometry {
             const uint32_t o = ok[c] ? off : (uint32_t)(lane & 15) * E;
             lane_byte[c] = o * BITS / 8;
             elem[c] = tile + o;
-            blk[c] = elem[c] >> log2b;
+            blk[c] = POW2 ? elem[c] >> log2b : (uint64_t)fast_div((uint32_t)(elem[c] / (16 * E)), rows_per_block);
         }
     }
 };
@@ -1055,12 +1064,37 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce(const PeerTable P, in
     }
 }
 
-// qgz_intra_reduce for any other block size (not a power of two, or wider than a wave of
-// 16-byte vectors): one wave per block, 8 elements per lane and round, at most 8 rounds.  The
-// sums of the whole block wait in registers between the maximum and the encode.  The peers
-// are the outer loop: per peer one scale (the same for the whole wave) and one load per
-// round, all issued before the first decode.
-template <int BITS>
+// qgz_intra_reduce for any other block size (not a power of two, or large): one wave per
+// block, 8 elements per lane and round, R <= 8 rounds
+// ((R-1)*64 < B/8 <= R*64).  The sums of the whole block wait in registers between the
+// maximum and the encode.  The peers are the outer loop: per peer one scale (the same for the
+// whole wave) and one load per round; the next peer's loads are issued before the current
+// peer is decoded (two register sets), and nothing inside the loop branches around a load, so
+// the wait before a decode covers that peer's loads only.  Lanes past the end of the block
+// fetch and decode piece 0 again; their sums are left out of the maximum and not stored.
+template <int NW, int R>
+__device__ __forceinline__ void load_block_rounds(const uint8_t* __restrict__ src, const uint32_t (&off)[R],
+                                                  uint32_t (&w)[R][NW])
+{
+#pragma unroll
+    for (int r = 0; r < R; ++r) load_words<NW>(src + off[r], w[r]);
+}
+
+// int4: the exact fused decode, valid for |s| < 2^100 (the caller redoes the block otherwise)
+template <int BITS, int NW, int R, bool FIRST>
+__device__ __forceinline__ void add_block_rounds(float (&acc)[R][8], const uint32_t (&w)[R][NW], float s)
+{
+    if constexpr (BITS == 4) {
+        const Dec4 op = dec4_operands(s);
+#pragma unroll
+        for (int r = 0; r < R; ++r) add_nibbles8<FIRST>(acc[r], w[r][0], op);
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) accumulate_plain<BITS, NW, FIRST>(acc[r], w[r], s);
+    }
+}
+
+template <int BITS, int R>
 __global__ __launch_bounds__(kThreads) void k_intra_reduce_anyblock(const PeerTable P, int K, uint32_t B,
                                                                     uint64_t blocks,
                                                                     uint8_t* __restrict__ codes_out,
@@ -1072,41 +1106,64 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce_anyblock(const PeerTa
     if (blk >= blocks) return;
     const uint32_t chunks = B / 8;  // 8-element pieces of the block
     const uint64_t base_byte = blk * B * BITS / 8;
-    uint32_t off[kBlockRounds];  // byte offset of the lane's piece in each round (lanes past the end repeat piece 0)
+    uint32_t off[R];  // byte offset of the lane's piece in each round
 #pragma unroll
-    for (int r = 0; r < kBlockRounds; ++r) {
+    for (int r = 0; r < R; ++r) {
         const uint32_t c = (uint32_t)r * kWave + lane;
         off[r] = (c < chunks ? c : 0u) * (uint32_t)BITS;
     }
-    float acc[kBlockRounds][8];
-    for (int k = 0; k < K; ++k) {
-        const float s = P.scales[k][blk];
-        const uint8_t* src = P.codes[k] + base_byte;
-        uint32_t w[kBlockRounds][NW];
+    float acc[R][8];
+    uint32_t wa[R][NW], wb[R][NW];
+    // entries of the table past the last peer repeat it, so peer 1 and the peer fetched ahead
+    // in the loop exist for every K
+    load_block_rounds<NW, R>(P.codes[0] + base_byte, off, wa);
+    float sa = P.scales[0][blk];
+    load_block_rounds<NW, R>(P.codes[1] + base_byte, off, wb);
+    float sb = P.scales[1][blk];
+    add_block_rounds<BITS, NW, R, true>(acc, wa, sa);
+    bool exact = dec4_exact(sa);  // of all scales so far (same in every lane)
+    int k = 1;                    // peers done; peer k waits in wb
+    for (; k + 1 < K; k += 2) {
+        load_block_rounds<NW, R>(P.codes[k + 1] + base_byte, off, wa);
+        sa = P.scales[k + 1][blk];
+        add_block_rounds<BITS, NW, R, false>(acc, wb, sb);
+        exact &= dec4_exact(sb);
+        const int ahead = k + 2 < ZPP_MAX_PEERS ? k + 2 : ZPP_MAX_PEERS - 1;
+        load_block_rounds<NW, R>(P.codes[ahead] + base_byte, off, wb);
+        sb = P.scales[ahead][blk];
+        add_block_rounds<BITS, NW, R, false>(acc, wa, sa);
+        exact &= dec4_exact(sa);
+    }
+    if (k < K) {
+        add_block_rounds<BITS, NW, R, false>(acc, wb, sb);
+        exact &= dec4_exact(sb);
+    }
+    if (BITS == 4 && !exact) {  // a scale of 2^100 or more: the whole block again, by convert and multiply
+        load_block_rounds<NW, R>(P.codes[0] + base_byte, off, wa);
+        sa = P.scales[0][blk];
 #pragma unroll
-        for (int r = 0; r < kBlockRounds; ++r)
-            if ((uint32_t)r * kWave < chunks) load_words<NW>(src + off[r], w[r]);
+        for (int r = 0; r < R; ++r) accumulate_plain<BITS, NW, true>(acc[r], wa[r], sa);
+        for (k = 1; k < K; ++k) {
+            load_block_rounds<NW, R>(P.codes[k] + base_byte, off, wa);
+            sa = P.scales[k][blk];
 #pragma unroll
-        for (int r = 0; r < kBlockRounds; ++r)
-            if ((uint32_t)r * kWave < chunks) {
-                if (k == 0) accumulate<BITS, NW, true>(acc[r], w[r], s);
-                else accumulate<BITS, NW, false>(acc[r], w[r], s);
-            }
+            for (int r = 0; r < R; ++r) accumulate_plain<BITS, NW, false>(acc[r], wa[r], sa);
+        }
     }
     float a = 0.0f;
 #pragma unroll
-    for (int r = 0; r < kBlockRounds; ++r) {
+    for (int r = 0; r < R; ++r) {
         const uint32_t c = (uint32_t)r * kWave + lane;
-        if ((uint32_t)r * kWave < chunks && c < chunks) a = fmaxf(a, absmax8(acc[r]));
+        if (c < chunks) a = fmaxf(a, absmax8(acc[r]));
     }
     a = group_max<kWave>(a);
     float scale, inv;
     block_scale<BITS>(a, scale, inv);
     if (lane == 0) scales_out[blk] = scale;
 #pragma unroll
-    for (int r = 0; r < kBlockRounds; ++r) {
+    for (int r = 0; r < R; ++r) {
         const uint32_t c = (uint32_t)r * kWave + lane;
-        if ((uint32_t)r * kWave < chunks && c < chunks) store_codes8<BITS>(codes_out, blk * B + c * 8u, acc[r], inv);
+        if (c < chunks) store_codes8<BITS>(codes_out, blk * B + c * 8u, acc[r], inv);
     }
 }
 
@@ -1196,9 +1253,10 @@ __global__ __launch_bounds__(kThreads) void k_selfcheck_divide(float d, float y,
 
 // qgz_inter_reduce, row form: element-wise, the block only selects the scale.  A wave sums
 // C vectors of 64 x E elements (a tile of C * 64 * E consecutive elements).
-template <int BITS, int NW, int C, int U>
+template <int BITS, int NW, int C, int U, bool POW2>
 __global__ __launch_bounds__(kThreads) void k_inter_reduce_rows(const PeerTable P, int K, uint64_t m, int log2b,
-                                                                float divisor, float recip, int recip_kind,
+                                                                FastDiv rows_per_block, float divisor, float recip,
+                                                                int recip_kind,
                                                                 uint32_t groups_per_xcd, int xcd_shift,
                                                                 float* __restrict__ out)
 {
@@ -1214,7 +1272,7 @@ __global__ __launch_bounds__(kThreads) void k_inter_reduce_rows(const PeerTable 
                                           : logical_block(xcd_shift);
     const uint64_t tile = (group * kWavesPerWG + wave) * ((uint64_t)C * kWave * E);
     if (tile >= m) return;
-    RowGeometry<BITS, NW, C> g(tile, m, log2b, lane);
+    RowGeometry<BITS, NW, C, POW2> g(tile, m, log2b, rows_per_block, lane);
     float acc[C][E];
     const bool mid = reduce_rows<BITS, NW, C, U>(P, K, tile * BITS / 8, g.lane_byte, g.elem, g.blk, lane,
                                                  reinterpret_cast<float*>(lds[wave]), acc);
@@ -1228,8 +1286,9 @@ __global__ __launch_bounds__(kThreads) void k_inter_reduce_rows(const PeerTable 
     }
 }
 
-// qgz_inter_reduce for any block size: a lane sums the 8 (int4) or 4 (int8) consecutive
-// elements of one code dword per peer and fetches its own scales.
+// qgz_inter_reduce for the remaining block sizes (not a whole number of 16-lane rows): a lane
+// sums the 8 (int4) or 4 (int8) consecutive elements of one code dword per peer and fetches
+// its own scales.
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void k_inter_reduce(const PeerTable P, int K, uint64_t m, uint32_t B,
                                                            int log2b, float divisor, float recip, int recip_kind,
@@ -1329,7 +1388,16 @@ int launch_quantize(const void* x, uint8_t* codes, float* scales, uint64_t L, ui
     const uint64_t blocks = L / B * slices;
     const uint64_t grid = ((blocks + kWavesPerWG - 1) / kWavesPerWG);
     if (grid > kMaxGrid) return ZPP_EINVAL;
-    k_quantize_anyblock<DT, BITS><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, B, blocks, X, Y);
+    if (blocks >= (1ull << 32)) return ZPP_EINVAL;  // more than any device buffer holds; slices and blocks per slice are smaller still
+    const uint32_t rounds = (B / 8 + kWave - 1) / kWave;
+    const FastDiv by_bps = make_fastdiv((uint32_t)(L / B)), byT = make_fastdiv(X * Y), byY = make_fastdiv(Y);
+#define ZPP_QA(R)                                                                                                   \
+    k_quantize_anyblock<DT, BITS, R><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(x, codes, scales, L, B, blocks, X, \
+                                                                                       Y, by_bps, byT, byY)
+    if (rounds <= 2) ZPP_QA(2);
+    else if (rounds <= 4) ZPP_QA(4);
+    else ZPP_QA(8);
+#undef ZPP_QA
     return launch_status();
 }
 
@@ -1359,6 +1427,11 @@ int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* cod
                  hipStream_t st)
 {
     constexpr int E = EPL<BITS, kIntraNW>::value;
+    // Largest power-of-two block that takes the kernel with lane-owned vectors.  From there
+    // on one wave per block with the scale in a scalar register is as fast or faster
+    // (measured at 2^25 and 2^27 elements: int4 1024 -2 %, 2048 +1 to +8 %; int8 256 -25 %,
+    // 512 +4 to +13 %, 1024 +5 to +8 %).
+    constexpr int kLaneVectorMaxBlock = BITS == 4 ? 1024 : 256;
     const int l2 = log2_or_neg(B);
     if (m / B > kMaxGrid) return ZPP_EINVAL;
     const uint64_t waves = (m + (uint64_t)kWave * E - 1) / ((uint64_t)kWave * E);
@@ -1366,25 +1439,38 @@ int launch_intra(const PeerTable& P, int K, uint64_t m, uint32_t B, uint8_t* cod
     if (grid > kMaxGrid) return ZPP_EINVAL;
 #define ZPP_I(L2)                                                                                                    \
     case L2:                                                                                                         \
-        if constexpr ((1 << L2) >= E && (1 << L2) <= kWave * E) {                                                    \
+        if constexpr ((1 << L2) >= E && (1 << L2) <= kLaneVectorMaxBlock) {                                          \
             k_intra_reduce<BITS, L2, kIntraNW><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(P, K, m, codes_out, scales_out); \
             return launch_status();                                                                                  \
         }                                                                                                            \
         break
-    switch (l2) {  // power-of-two blocks of at most one wave
+    switch (l2) {  // small power-of-two blocks
         ZPP_I(5);
         ZPP_I(6);
         ZPP_I(7);
         ZPP_I(8);
         ZPP_I(9);
         ZPP_I(10);
-        ZPP_I(11);
     default: break;
     }
 #undef ZPP_I
     const uint64_t blocks = m / B, groups = (blocks + kWavesPerWG - 1) / kWavesPerWG;
-    k_intra_reduce_anyblock<BITS><<<dim3((uint32_t)groups), dim3(kThreads), 0, st>>>(P, K, B, blocks, codes_out, scales_out);
-    return launch_status();
+#define ZPP_IA(R)                                                                                                    \
+    case R:                                                                                                          \
+        k_intra_reduce_anyblock<BITS, R><<<dim3((uint32_t)groups), dim3(kThreads), 0, st>>>(P, K, B, blocks, codes_out, scales_out); \
+        return launch_status()
+    switch ((B / 8 + kWave - 1) / kWave) {  // rounds of 64 lanes x 8 elements that cover a block
+        ZPP_IA(1);
+        ZPP_IA(2);
+        ZPP_IA(3);
+        ZPP_IA(4);
+        ZPP_IA(5);
+        ZPP_IA(6);
+        ZPP_IA(7);
+        ZPP_IA(8);
+    default: return ZPP_EINVAL;  // unreachable: blocks have at most 4096 elements
+    }
+#undef ZPP_IA
 }
 
 // divisor of qgz_inter_reduce as the kernels take it
@@ -1408,8 +1494,10 @@ Divisor prepare_divisor(float d)
 }
 
 template <int BITS, int C, int U>
-int launch_inter_rows(const PeerTable& P, int K, uint64_t m, int l2, const Divisor& dv, float* out, hipStream_t st)
+int launch_inter_rows(const PeerTable& P, int K, uint64_t m, uint32_t B, const Divisor& dv, float* out, hipStream_t st)
 {
+    const int l2 = log2_or_neg(B);
+    const FastDiv rows_per_block = make_fastdiv(B / (16 * EPL<BITS, 1>::value));
     constexpr uint64_t tile = (uint64_t)C * kWave * EPL<BITS, 1>::value;
     const uint64_t waves = (m + tile - 1) / tile;
     const uint64_t groups = (waves + kWavesPerWG - 1) / kWavesPerWG;
@@ -1421,8 +1509,12 @@ int launch_inter_rows(const PeerTable& P, int K, uint64_t m, int l2, const Divis
         grid = per_xcd * 8;
     }
     if (grid > kMaxGrid) return ZPP_EINVAL;
-    k_inter_reduce_rows<BITS, 1, C, U><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
-        P, K, m, l2, dv.d, dv.recip, dv.kind, (uint32_t)per_xcd, xcd_shift, out);
+    if (l2 >= 0)
+        k_inter_reduce_rows<BITS, 1, C, U, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+            P, K, m, l2, rows_per_block, dv.d, dv.recip, dv.kind, (uint32_t)per_xcd, xcd_shift, out);
+    else
+        k_inter_reduce_rows<BITS, 1, C, U, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+            P, K, m, l2, rows_per_block, dv.d, dv.recip, dv.kind, (uint32_t)per_xcd, xcd_shift, out);
     return launch_status();
 }
 
@@ -1457,12 +1549,14 @@ int launch_inter(const PeerTable& P, int K, uint64_t m, uint32_t B, const Diviso
 {
     constexpr uint32_t E = EPL<BITS, 1>::value;
     const int l2 = log2_or_neg(B);
-    if (l2 >= 0 && B >= 16 * E) {  // a row of 16 lanes inside one block: the row form
+    // a row of 16 lanes inside one block: the row form (blocks that are not powers of two
+    // find their scales by a 32-bit division of the row index)
+    if (B % (16 * E) == 0 && (l2 >= 0 || m / (16 * E) < (1ull << 32))) {
         const int c = inter_rows_vectors((m + kWave * E - 1) / (kWave * E));
         // peers per fetch group: 8 where a wave has one vector (more bytes in flight per wave), 4 otherwise
-        if (c == 1) return launch_inter_rows<BITS, 1, 8>(P, K, m, l2, dv, out, st);
-        if (c == 2) return launch_inter_rows<BITS, 2, 4>(P, K, m, l2, dv, out, st);
-        return launch_inter_rows<BITS, 3, 4>(P, K, m, l2, dv, out, st);
+        if (c == 1) return launch_inter_rows<BITS, 1, 8>(P, K, m, B, dv, out, st);
+        if (c == 2) return launch_inter_rows<BITS, 2, 4>(P, K, m, B, dv, out, st);
+        return launch_inter_rows<BITS, 3, 4>(P, K, m, B, dv, out, st);
     }
     constexpr uint64_t per_wave = (uint64_t)kWave * E;
     const uint64_t waves = (m + per_wave - 1) / per_wave;

@@ -280,6 +280,21 @@ INTRA_CASES = [
     (8, 2048, 8, 5),      # int8: wider than a wave of 16-byte vectors
     (3, 4096, 8, 3),
     (6, 1056, 8, 13),
+    # one wave per block, every number of rounds (1..8) at both widths; peers fetched one
+    # ahead in pairs: odd and even counts, one peer, the full table
+    (3, 480, 4, 9),
+    (4, 992, 4, 7),
+    (1, 1536, 4, 5),
+    (9, 2016, 4, 6),
+    (64, 2528, 4, 3),
+    (2, 3072, 4, 4),
+    (63, 3552, 4, 2),
+    (7, 480, 8, 5),
+    (2, 1504, 8, 5),
+    (5, 2528, 8, 3),
+    (64, 3040, 8, 2),
+    (6, 3552, 8, 3),
+    (1, 4096, 8, 2),
 ]
 
 
@@ -296,6 +311,24 @@ def test_qgz_intra_reduce_bit_exact(X, block, bits, blocks):
     assert eq_bytes(codes, want_codes), "codes differ"
     assert_guards_intact(cfull, m * bits // 8, torch.uint8)
     assert_guards_intact(sfull, m // block, torch.float32)
+
+
+@pytest.mark.parametrize("X,block,blocks", [(8, 4096, 6), (5, 1536, 9), (2, 96, 40), (8, 512, 12)])
+def test_qgz_intra_reduce_with_scales_beyond_the_exact_int4_decode(X, block, blocks):
+    """Scales of 2^100 and more (never produced from 16-bit gradients) leave the fused int4
+    decode: the block is then summed by convert and multiply.  One such scale per block, of
+    either sign, in some blocks; the outputs are the oracle's bit for bit."""
+    m, bits = block * blocks, 4
+    host, dev = _peer_inputs(X, m, block, bits, seed=31 + block)
+    scales = [h[1].copy() for h in host]
+    for b in range(0, blocks, 2):
+        scales[(b // 2) % X][b] = np.float32(2.0 ** 101 if b % 4 == 0 else -(2.0 ** 118))
+    want_codes, want_scales = oracle.qgz_intra_reduce([h[0] for h in host], scales, m, block, bits)
+    got_codes, got_scales = zpp.qgz_intra_reduce([d[0] for d in dev], [torch.from_numpy(s).to(DEV) for s in scales],
+                                                 m, block, bits)
+    torch.cuda.synchronize()
+    assert eq_bytes(got_scales, want_scales), "scales differ"
+    assert eq_bytes(got_codes, want_codes), "codes differ"
 
 
 INTER_CASES = [
@@ -565,6 +598,31 @@ def test_qgz_inter_reduce_across_launch_shapes(Y, blocks, div):
     block, bits = 512, 4
     m = block * blocks
     host, dev = _peer_inputs(Y, m, block, bits, seed=Y + blocks)
+    want = oracle.qgz_inter_reduce([h[0] for h in host], [h[1] for h in host], m, block, bits, div)
+    ofull, out = guarded(m, torch.float32)
+    zpp.qgz_inter_reduce([d[0] for d in dev], [d[1] for d in dev], m, block, bits, div, out=out)
+    torch.cuda.synchronize()
+    assert eq_bytes(out, want)
+    assert_guards_intact(ofull, m, torch.float32)
+
+
+@pytest.mark.parametrize("Y,block,bits,blocks,div", [
+    (48, 1536, 4, 7, 384.0),       # 12 rows of 128 elements per block
+    (5, 384, 4, 33, 5.0),
+    (64, 3200, 4, 3, 3.0),
+    (3, 1536, 4, 3072, 384.0),     # 9216 wave tiles: three vectors per wave
+    (2, 640, 4, 8192, 7.0),        # 10240 wave tiles: two vectors per wave
+    (2, 1536, 4, 4097, 3.0),       # 12291 wave tiles: one vector per wave, large grid
+    (6, 192, 8, 50, 48.0),         # int8: rows of 64 elements
+    (3, 4032, 8, 2, 7.25),
+    (2, 576, 8, 4096, 24.0),       # int8, 9216 wave tiles
+])
+def test_qgz_inter_reduce_blocks_of_whole_rows_that_are_not_powers_of_two(Y, block, bits, blocks, div):
+    """Blocks that are a whole number of 16-lane rows (128 int4 or 64 int8 elements) but not a
+    power of two take the same kernels as the powers of two, with the block of a row found by
+    a division prepared on the host; every launch shape of those kernels."""
+    m = block * blocks
+    host, dev = _peer_inputs(Y, m, block, bits, seed=Y + block)
     want = oracle.qgz_inter_reduce([h[0] for h in host], [h[1] for h in host], m, block, bits, div)
     ofull, out = guarded(m, torch.float32)
     zpp.qgz_inter_reduce([d[0] for d in dev], [d[1] for d in dev], m, block, bits, div, out=out)
