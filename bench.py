@@ -591,7 +591,44 @@ def per_config_kernels(torch, zpp, workloads, dev, runner):
     tb = zpp.PeerTable([e[0] for e in enc], [e[1] for e in enc])
     run("generic.qgz_inter_reduce_block96", Bytes.inter(Lg, 96, 4, 48),
         lambda: zpp.qgz_inter_reduce(tb, None, Lg, 96, 4, 384.0, out=og), "every lane fetches its own scales")
-    del enc, tb, og, gq, qc, qs, grads, first, co, so, tables
+    del enc, tb, og, gq, qc, qs
+
+    # the variants the same entry points take by argument, at the same sizes: the gradient path with int8
+    # codes, the one-hop reduction (the second-hop kernel over all ranks at once: 64 of them here, the most
+    # one call takes), and the weight path with int4 codes and with fp32 weights
+    g8 = [zpp.qgz_reorder(g, X, Y, 1, B, 8) for g in grads[:2]]
+    run("variants.qgz_reorder_int8", Bytes.quantize(n, B, 8),
+        lambda: zpp.qgz_reorder(grads[0], X, Y, 1, B, 8, codes=g8[0][0], scales=g8[0][1]))
+    co8 = torch.empty(m, dtype=torch.uint8, device=dev)
+    tb = zpp.PeerTable([g8[k % 2][0][(k // 2) * m:(k // 2 + 1) * m] for k in range(X)],
+                       [g8[k % 2][1][(k // 2) * sb:(k // 2 + 1) * sb] for k in range(X)])
+    run("variants.qgz_intra_reduce_int8", Bytes.intra(m, B, 8, X),
+        lambda: zpp.qgz_intra_reduce(tb, None, m, B, 8, codes_out=co8, scales_out=so),
+        "int8 blocks of 512 and more take the wave-per-block kernel")
+    og = torch.empty(Lg, dtype=torch.float32, device=dev)
+    tb = zpp.PeerTable([g8[k % 2][0][(k // 2) * Lg:(k // 2 + 1) * Lg] for k in range(48)],
+                       [g8[k % 2][1][(k // 2) * (Lg // B):(k // 2 + 1) * (Lg // B)] for k in range(48)])
+    run("variants.qgz_inter_reduce_int8", Bytes.inter(Lg, B, 8, 48),
+        lambda: zpp.qgz_inter_reduce(tb, None, Lg, B, 8, 384.0, out=og))
+    del g8, co8, tb
+    tb = zpp.PeerTable([first[k % X][0][(k // X) * (Lg // 2):(k // X + 1) * (Lg // 2)] for k in range(64)],
+                       [first[k % X][1][(k // X) * (Lg // B):(k // X + 1) * (Lg // B)] for k in range(64)])
+    run("variants.qgz_inter_reduce_one_hop_64_ranks", Bytes.inter(Lg, B, 4, 64),
+        lambda: zpp.qgz_inter_reduce(tb, None, Lg, B, 4, 64.0, out=og), "Sec. 3.3.1: every rank's slice reduced in one hop")
+    del tb, og, grads, first, co, so, tables
+    wn = 1 << 28
+    wb = workloads.weights(wn, device=dev, tensor_id=12)
+    c4, s4 = zpp.qwz_quantize(wb, 2048, 4)
+    run("variants.qwz_quantize_int4", Bytes.quantize(wn, 2048, 4), lambda: zpp.qwz_quantize(wb, 2048, 4, codes=c4, scales=s4))
+    run("variants.qwz_dequantize_int4", Bytes.dequantize(wn, 2048, 4), lambda: zpp.qwz_dequantize(c4, s4, wn, 2048, 4, out=wb))
+    del wb, c4, s4
+    wf = workloads.weights(wn, device=dev, tensor_id=13, dtype=torch.float32)
+    c8, s8 = zpp.qwz_quantize(wf, 2048, 8)
+    run("variants.qwz_quantize_fp32_weights", Bytes.quantize(wn, 2048, 8, in_bytes=4),
+        lambda: zpp.qwz_quantize(wf, 2048, 8, codes=c8, scales=s8))
+    run("variants.qwz_dequantize_to_fp32", Bytes.dequantize(wn, 2048, 8, out_bytes=4),
+        lambda: zpp.qwz_dequantize(c8, s8, wn, 2048, 8, out=wf))
+    del wf, c8, s8
 
     # configs[3]: 48 node chunks of 46,875,136 elements (46,875,000 padded to the block), int4 block 512.
     # The chunks sit one after the other in one receive buffer for the codes and one for the scales, as

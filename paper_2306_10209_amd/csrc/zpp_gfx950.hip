@@ -162,6 +162,60 @@ __device__ __forceinline__ void load8(const void* __restrict__ base, uint64_t e,
     }
 }
 
+// fp32 tensors: a lane's 8 consecutive elements are 32 bytes, so a wave-wide 16-byte access by
+// "lane l takes elements 8l.." touches every other 16 bytes of 2 KB.  Instead every load or
+// store instruction moves one contiguous KB (lane l: 16-byte chunk l, then chunk 64 + l, of
+// the wave's run of 512 elements) and the chunks change lanes through 2 KB of LDS.
+//
+// Slot of chunk c in that buffer: rows of 8 chunks, the column XORed with the row, so that
+// "lane l touches chunk l" and "lane l touches chunk 2l (or 2l + 1)" both spread over all banks.
+__device__ __forceinline__ uint32_t turn_slot(uint32_t c) { return (c & ~7u) | ((c ^ (c >> 3)) & 7u); }
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The two chunks lane `lane` fetches of the run of `valid` (<= 512, a multiple of 8) fp32
+// elements at `run`; chunks past the end read as zero.
+__device__ __forceinline__ void load_run_f32(const float* __restrict__ run, uint32_t valid, int lane, f32x4& a, f32x4& b)
+{
+    const f32x4* p = reinterpret_cast<const f32x4*>(run);
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    a = (uint32_t)lane * 4u < valid ? ld_stream(p + lane) : zero;
+    b = (uint32_t)(kWave + lane) * 4u < valid ? ld_stream(p + kWave + lane) : zero;
+}
+
+// f = elements 8*lane .. 8*lane+7 of the run whose chunks lane and 64+lane are a and b in every lane
+__device__ __forceinline__ void turn_to_lanes(const f32x4& a, const f32x4& b, int lane, f32x4* __restrict__ turn, float (&f)[8])
+{
+    turn[turn_slot((uint32_t)lane)] = a;
+    turn[turn_slot((uint32_t)(kWave + lane))] = b;
+    wave_lds_fence();
+    const f32x4 u = turn[turn_slot(2u * lane)], v = turn[turn_slot(2u * lane + 1u)];
+    wave_lds_fence();
+    f[0] = u.x; f[1] = u.y; f[2] = u.z; f[3] = u.w;
+    f[4] = v.x; f[5] = v.y; f[6] = v.z; f[7] = v.w;
+}
+
+// The reverse: d = elements 8*lane .. 8*lane+7 of a run of `valid` fp32 elements at `run`, stored
+// as two contiguous KB per wave.
+__device__ __forceinline__ void store_run_f32(const float (&d)[8], float* __restrict__ run, uint32_t valid, int lane,
+                                              f32x4* __restrict__ turn)
+{
+    const f32x4 u = {d[0], d[1], d[2], d[3]}, v = {d[4], d[5], d[6], d[7]};
+    turn[turn_slot(2u * lane)] = u;
+    turn[turn_slot(2u * lane + 1u)] = v;
+    wave_lds_fence();
+    const f32x4 a = turn[turn_slot((uint32_t)lane)], b = turn[turn_slot((uint32_t)(kWave + lane))];
+    wave_lds_fence();
+    f32x4* o = reinterpret_cast<f32x4*>(run);
+    if ((uint32_t)lane * 4u < valid) st_stream(a, o + lane);
+    if ((uint32_t)(kWave + lane) * 4u < valid) st_stream(b, o + kWave + lane);
+}
+
 // ---------------------------------------------------------------------------
 // block codec pieces
 // ---------------------------------------------------------------------------
@@ -346,22 +400,36 @@ __device__ __host__ __forceinline__ uint64_t source_slice32(uint32_t p, uint32_t
 template <int DT, int BITS, int LOG2B, int V, bool FULL, bool DEEP>
 __device__ __forceinline__ void quantize_tile(const void* __restrict__ x, uint8_t* __restrict__ codes,
                                               float* __restrict__ scales, uint64_t in_base, uint64_t out_base,
-                                              uint64_t rem, int lane)
+                                              uint64_t rem, int lane, f32x4* __restrict__ turn /* fp32 input: 2 KB of LDS */)
 {
     constexpr int B = 1 << LOG2B;
     float f[V][8];
     bool ok[V];
+    if constexpr (DT == ZPP_F32) {
+        f32x4 qa[V], qb[V];
 #pragma unroll
-    for (int k = 0; k < V; ++k) {
-        const uint32_t off = (uint32_t)(k * kWave + lane) * 8u;
-        ok[k] = FULL || off < rem;
-        if (ok[k]) {
-            load8<DT>(x, in_base + off, f[k]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) f[k][i] = 0.0f;
+        for (int k = 0; k < V; ++k) {
+            const uint32_t first = (uint32_t)k * 512u;  // of this step's run
+            const uint32_t valid = FULL ? 512u : (rem > first ? (rem - first < 512 ? (uint32_t)(rem - first) : 512u) : 0u);
+            ok[k] = FULL || (uint32_t)(k * kWave + lane) * 8u < rem;
+            load_run_f32(static_cast<const float*>(x) + in_base + first, valid, lane, qa[k], qb[k]);
+            if (!DEEP) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         }
-        if (!DEEP) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+#pragma unroll
+        for (int k = 0; k < V; ++k) turn_to_lanes(qa[k], qb[k], lane, turn, f[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const uint32_t off = (uint32_t)(k * kWave + lane) * 8u;
+            ok[k] = FULL || off < rem;
+            if (ok[k]) {
+                load8<DT>(x, in_base + off, f[k]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) f[k][i] = 0.0f;
+            }
+            if (!DEEP) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        }
     }
 
     if constexpr (B >= 512) {
@@ -414,10 +482,15 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void* __restrict__ 
     const uint64_t in_base = src * L + (uint64_t)t * TILE;
     const uint64_t out_base = (uint64_t)p * L + (uint64_t)t * TILE;
     const uint64_t rem = L - (uint64_t)t * TILE;  // elements of this slice from the tile start on (>= 1)
+    f32x4* turn = nullptr;
+    if constexpr (DT == ZPP_F32) {
+        __shared__ f32x4 turn_lds[kWavesPerWG][2 * kWave];
+        turn = turn_lds[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+    }
     if (rem >= TILE)
-        quantize_tile<DT, BITS, LOG2B, V, true, DEEP>(x, codes, scales, in_base, out_base, rem, lane);
+        quantize_tile<DT, BITS, LOG2B, V, true, DEEP>(x, codes, scales, in_base, out_base, rem, lane, turn);
     else
-        quantize_tile<DT, BITS, LOG2B, V, false, DEEP>(x, codes, scales, in_base, out_base, rem, lane);
+        quantize_tile<DT, BITS, LOG2B, V, false, DEEP>(x, codes, scales, in_base, out_base, rem, lane, turn);
 }
 
 // Any other block size that is a multiple of 32 (not a power of two): one wave per block.
@@ -505,7 +578,7 @@ __device__ __forceinline__ float byte_f32(uint32_t w, int i)
 template <int ODT, int BITS, int V, bool POW2, bool ONE_BLOCK>
 __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ codes, const float* __restrict__ scales,
                                                 void* __restrict__ y, uint64_t base, uint64_t rem, uint32_t B,
-                                                int log2b, int lane)
+                                                int log2b, int lane, f32x4* __restrict__ turn /* fp32 output: 2 KB of LDS */)
 {
     uint32_t w[V][2];
     float s[V];
@@ -537,8 +610,12 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ code
     }
 #pragma unroll
     for (int k = 0; k < V; ++k) {
-        if (!ok[k]) continue;
-        float d[8];
+        if (ODT == ZPP_F32) {  // the whole wave takes part in the store: leave only when the step's run is empty
+            if ((uint64_t)k * 512u >= rem) break;
+        } else if (!ok[k]) {
+            continue;
+        }
+        float d[8];  // lanes past the end have zero codes and a zero scale
         if (BITS == 8) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -551,10 +628,8 @@ __device__ __forceinline__ void dequantize_tile(const uint8_t* __restrict__ code
         }
         const uint64_t e = base + (uint32_t)(k * kWave + lane) * 8u;
         if (ODT == ZPP_F32) {
-            f32x4* o = reinterpret_cast<f32x4*>(static_cast<float*>(y) + e);
-            f32x4 a = {d[0], d[1], d[2], d[3]}, b = {d[4], d[5], d[6], d[7]};
-            st_stream(a, o);
-            st_stream(b, o + 1);
+            const uint64_t first = (uint64_t)k * 512u, left = rem - first;
+            store_run_f32(d, static_cast<float*>(y) + base + first, left < 512 ? (uint32_t)left : 512u, lane, turn);
         } else {
             u32x4 o;
             o.x = narrow2<ODT>(d[0], d[1]);
@@ -577,7 +652,12 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const uint8_t* __restri
     const uint64_t wid = logical_block(xcd_shift) * kWavesPerWG + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t base = wid * TILE;
     if (base >= n) return;
-    dequantize_tile<ODT, BITS, V, POW2, ONE_BLOCK>(codes, scales, y, base, n - base, B, log2b, lane);
+    f32x4* turn = nullptr;
+    if constexpr (ODT == ZPP_F32) {
+        __shared__ f32x4 turn_lds[kWavesPerWG][2 * kWave];
+        turn = turn_lds[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+    }
+    dequantize_tile<ODT, BITS, V, POW2, ONE_BLOCK>(codes, scales, y, base, n - base, B, log2b, lane, turn);
 }
 
 // ---------------------------------------------------------------------------
