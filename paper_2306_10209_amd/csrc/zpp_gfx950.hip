@@ -704,7 +704,7 @@ __device__ __forceinline__ Dec4 dec4_operands(float s)
     d.bias = s * -8.0f;
     return d;
 }
-__device__ __forceinline__ bool dec4_exact(float s) { return fabsf(s) < 0x1p100f; }
+__device__ __forceinline__ bool fused_decode_ok(float s) { return fabsf(s) < 0x1p100f; }
 
 // acc[0..8) (+)= decode(nibble_i of w, s), i = 0..7 (nibble i = bits 4i..4i+3).
 //
@@ -740,6 +740,47 @@ __device__ __forceinline__ void add_nibbles8(float* __restrict__ acc, uint32_t w
     acc[7] = FIRST ? __builtin_fmaf((float)e.y, d.hi, d.bias) : acc[7] + __builtin_fmaf((float)e.y, d.hi, d.bias);
 }
 
+// The same decode for int8 codes: after flipping each byte's top bit the byte holds u = q + 128,
+// and a 16-bit lane whose only set bits are its low byte is the binary16 subnormal u*2^-24;
+// fma(u*2^-24, s*2^24, -128*s) = q*s rounded once.  Operands for |s| < 2^100:
+struct Dec8 {
+    float lo, bias;
+};
+__device__ __forceinline__ Dec8 dec8_operands(float s)
+{
+    Dec8 d;
+    d.lo = s * 0x1p24f;
+    d.bias = s * -128.0f;
+    return d;
+}
+
+// acc[0..4) (+)= decode(byte_i of w, s), i = 0..3.  FIRST as in add_nibbles8 (never -0 either).
+template <bool FIRST>
+__device__ __forceinline__ void add_bytes4(float* __restrict__ acc, uint32_t w, const Dec8& d)
+{
+    const f16x2 a = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(w, 0x80808080u, 0x00FF00FFu, 0x28));       // elements 0, 2
+    const f16x2 b = __builtin_bit_cast(f16x2, __builtin_amdgcn_bitop3_b32(w >> 8, 0x80808080u, 0x00FF00FFu, 0x28));  // elements 1, 3
+    acc[0] = FIRST ? __builtin_fmaf((float)a.x, d.lo, d.bias) : acc[0] + __builtin_fmaf((float)a.x, d.lo, d.bias);
+    acc[1] = FIRST ? __builtin_fmaf((float)b.x, d.lo, d.bias) : acc[1] + __builtin_fmaf((float)b.x, d.lo, d.bias);
+    acc[2] = FIRST ? __builtin_fmaf((float)a.y, d.lo, d.bias) : acc[2] + __builtin_fmaf((float)a.y, d.lo, d.bias);
+    acc[3] = FIRST ? __builtin_fmaf((float)b.y, d.lo, d.bias) : acc[3] + __builtin_fmaf((float)b.y, d.lo, d.bias);
+}
+
+// acc[i] (+)= decode(code_i, s) for the codes of NW dwords by the fused decodes above (|s| < 2^100)
+template <int BITS, int NW, bool FIRST>
+__device__ __forceinline__ void accumulate_fused(float* __restrict__ acc, const uint32_t (&d)[NW], float s)
+{
+    if constexpr (BITS == 4) {
+        const Dec4 op = dec4_operands(s);
+#pragma unroll
+        for (int j = 0; j < NW; ++j) add_nibbles8<FIRST>(acc + j * 8, d[j], op);
+    } else {
+        const Dec8 op = dec8_operands(s);
+#pragma unroll
+        for (int j = 0; j < NW; ++j) add_bytes4<FIRST>(acc + j * 4, d[j], op);
+    }
+}
+
 // acc[i] (+)= float(code_i) * s for the codes of NW dwords by convert and multiply (any
 // scale).  The product can be -0 (code 0 and a negative scale, a negative code and a zero
 // scale), so the first peer is added to the +0 the sum starts from.
@@ -764,11 +805,9 @@ __device__ __forceinline__ void accumulate_plain(float (&acc)[(EPL<BITS, NW>::va
 template <int BITS, int NW, bool FIRST>
 __device__ __forceinline__ void accumulate(float (&acc)[(EPL<BITS, NW>::value)], const uint32_t (&d)[NW], float s)
 {
-    if (BITS == 4 && dec4_exact(s)) {
-        const Dec4 op = dec4_operands(s);
-#pragma unroll
-        for (int j = 0; j < NW; ++j) add_nibbles8<FIRST>(acc + j * 8, d[j], op);
-    } else {  // int8, and int4 scales so large that they never come from 16-bit gradients
+    if (fused_decode_ok(s)) {
+        accumulate_fused<BITS, NW, FIRST>(acc, d, s);
+    } else {  // scales so large that they never come from 16-bit gradients
         accumulate_plain<BITS, NW, FIRST>(acc, d, s);
     }
 }
@@ -874,12 +913,12 @@ __device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, ui
 // the loop, so the wait before a decode never includes the loads issued after it.
 
 // One wave's table: [row r][peer k][vector c][operand], PL operands per peer and vector (int4:
-// s * 2^24, s * 2^20, -8 s; int8: s), so that what one peer needs, and what a group of peers
+// s * 2^24, s * 2^20, -8 s; int8: s * 2^24, -128 s), so that what one peer needs, and what a group of peers
 // needs, is one short run behind one address.  The row pitch is odd, so the 4 rows, which are
 // read together, fall into different banks.
 template <int BITS, int C>
 struct RowTable {
-    static constexpr int PL = BITS == 4 ? 3 : 1;
+    static constexpr int PL = BITS == 4 ? 3 : 2;
     static constexpr int row_pitch = (ZPP_MAX_PEERS * C * PL) | 1;
     static constexpr int floats = 4 * row_pitch;
 };
@@ -909,7 +948,7 @@ __device__ __forceinline__ void row_scale_loads(const float* const (&sp)[kRowChu
 
 // What a wave learns about its scales while it writes its table.
 struct RowScaleFacts {
-    bool exact;  // every int4 scale can take the exact decode (else the table must not be used)
+    bool exact;  // every scale can take the fused decode (else the table must not be used)
     bool mid;    // every scale is 0 or 2^-30 <= |s| < 2^60: nonzero sums then lie in [2^-53, 2^69)
 };
 
@@ -928,21 +967,23 @@ __device__ __forceinline__ RowScaleFacts write_row_table(const float (&s)[kRowCh
             float* t = tab + row * T::row_pitch + ((i * 16 + j) * C + c) * T::PL;
             const float mag = fabsf(s[i][c]);
             mid = mid && (mag == 0.0f || (mag >= 0x1p-30f && mag < 0x1p60f));
+            fine = fine && fused_decode_ok(s[i][c]);
             if (BITS == 4) {
                 const Dec4 op = dec4_operands(s[i][c]);
-                fine = fine && dec4_exact(s[i][c]);
                 t[0] = op.lo;
                 t[1] = op.hi;
                 t[2] = op.bias;
             } else {
-                t[0] = s[i][c];
+                const Dec8 op = dec8_operands(s[i][c]);
+                t[0] = op.lo;
+                t[1] = op.bias;
             }
         }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     RowScaleFacts f;
-    f.exact = BITS != 4 || __builtin_amdgcn_ballot_w64(!fine) == 0;
+    f.exact = __builtin_amdgcn_ballot_w64(!fine) == 0;
     f.mid = __builtin_amdgcn_ballot_w64(!mid) == 0;
     return f;
 }
@@ -990,7 +1031,11 @@ __device__ __forceinline__ void add_group_rows(float (&acc)[C][(EPL<BITS, NW>::v
 #pragma unroll
                 for (int j = 0; j < NW; ++j) add_nibbles8<false>(acc[c] + j * 8, w[u][c][j], op);
             } else {
-                accumulate_plain<BITS, NW, false>(acc[c], w[u][c], tc[0]);
+                Dec8 op;
+                op.lo = tc[0];
+                op.bias = tc[1];
+#pragma unroll
+                for (int j = 0; j < NW; ++j) add_bytes4<false>(acc[c] + j * 4, w[u][c][j], op);
             }
         }
     }
@@ -1036,7 +1081,7 @@ __device__ __forceinline__ bool reduce_rows(const PeerTable& P, int K, uint64_t 
     if (n == 1) return false;
     const RowScaleFacts facts = write_row_table<BITS, C>(st, lane, tab);
     if (!facts.exact) {
-        // int4 scales of 2^100 and more: every lane decodes with its own scale loads
+        // scales of 2^100 and more: every lane decodes with its own scale loads, by convert and multiply
 #pragma unroll
         for (int c = 0; c < C; ++c) reduce_peers_plain<BITS, NW>(P, K, elem[c], blk[c], acc[c]);
         return false;
@@ -1160,7 +1205,7 @@ __device__ __forceinline__ void load_block_rounds(const uint8_t* __restrict__ sr
     for (int r = 0; r < R; ++r) load_words<NW>(src + off[r], w[r]);
 }
 
-// int4: the exact fused decode, valid for |s| < 2^100 (the caller redoes the block otherwise)
+// the fused decode, valid for |s| < 2^100 (the caller redoes the block otherwise)
 template <int BITS, int NW, int R, bool FIRST>
 __device__ __forceinline__ void add_block_rounds(float (&acc)[R][8], const uint32_t (&w)[R][NW], float s)
 {
@@ -1169,8 +1214,12 @@ __device__ __forceinline__ void add_block_rounds(float (&acc)[R][8], const uint3
 #pragma unroll
         for (int r = 0; r < R; ++r) add_nibbles8<FIRST>(acc[r], w[r][0], op);
     } else {
+        const Dec8 op = dec8_operands(s);
 #pragma unroll
-        for (int r = 0; r < R; ++r) accumulate_plain<BITS, NW, FIRST>(acc[r], w[r], s);
+        for (int r = 0; r < R; ++r) {
+            add_bytes4<FIRST>(acc[r], w[r][0], op);
+            add_bytes4<FIRST>(acc[r] + 4, w[r][1], op);
+        }
     }
 }
 
@@ -1201,24 +1250,24 @@ __global__ __launch_bounds__(kThreads) void k_intra_reduce_anyblock(const PeerTa
     load_block_rounds<NW, R>(P.codes[1] + base_byte, off, wb);
     float sb = P.scales[1][blk];
     add_block_rounds<BITS, NW, R, true>(acc, wa, sa);
-    bool exact = dec4_exact(sa);  // of all scales so far (same in every lane)
+    bool exact = fused_decode_ok(sa);  // of all scales so far (same in every lane)
     int k = 1;                    // peers done; peer k waits in wb
     for (; k + 1 < K; k += 2) {
         load_block_rounds<NW, R>(P.codes[k + 1] + base_byte, off, wa);
         sa = P.scales[k + 1][blk];
         add_block_rounds<BITS, NW, R, false>(acc, wb, sb);
-        exact &= dec4_exact(sb);
+        exact &= fused_decode_ok(sb);
         const int ahead = k + 2 < ZPP_MAX_PEERS ? k + 2 : ZPP_MAX_PEERS - 1;
         load_block_rounds<NW, R>(P.codes[ahead] + base_byte, off, wb);
         sb = P.scales[ahead][blk];
         add_block_rounds<BITS, NW, R, false>(acc, wa, sa);
-        exact &= dec4_exact(sa);
+        exact &= fused_decode_ok(sa);
     }
     if (k < K) {
         add_block_rounds<BITS, NW, R, false>(acc, wb, sb);
-        exact &= dec4_exact(sb);
+        exact &= fused_decode_ok(sb);
     }
-    if (BITS == 4 && !exact) {  // a scale of 2^100 or more: the whole block again, by convert and multiply
+    if (!exact) {  // a scale of 2^100 or more: the whole block again, by convert and multiply
         load_block_rounds<NW, R>(P.codes[0] + base_byte, off, wa);
         sa = P.scales[0][blk];
 #pragma unroll
@@ -1573,12 +1622,12 @@ Divisor prepare_divisor(float d)
     return v;
 }
 
-template <int BITS, int C, int U>
+template <int BITS, int NW, int C, int U>
 int launch_inter_rows(const PeerTable& P, int K, uint64_t m, uint32_t B, const Divisor& dv, float* out, hipStream_t st)
 {
     const int l2 = log2_or_neg(B);
-    const FastDiv rows_per_block = make_fastdiv(B / (16 * EPL<BITS, 1>::value));
-    constexpr uint64_t tile = (uint64_t)C * kWave * EPL<BITS, 1>::value;
+    const FastDiv rows_per_block = make_fastdiv(B / (16 * EPL<BITS, NW>::value));
+    constexpr uint64_t tile = (uint64_t)C * kWave * EPL<BITS, NW>::value;
     const uint64_t waves = (m + tile - 1) / tile;
     const uint64_t groups = (waves + kWavesPerWG - 1) / kWavesPerWG;
     // surplus groups of either padded grid exit at once
@@ -1590,10 +1639,10 @@ int launch_inter_rows(const PeerTable& P, int K, uint64_t m, uint32_t B, const D
     }
     if (grid > kMaxGrid) return ZPP_EINVAL;
     if (l2 >= 0)
-        k_inter_reduce_rows<BITS, 1, C, U, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+        k_inter_reduce_rows<BITS, NW, C, U, true><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
             P, K, m, l2, rows_per_block, dv.d, dv.recip, dv.kind, (uint32_t)per_xcd, xcd_shift, out);
     else
-        k_inter_reduce_rows<BITS, 1, C, U, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
+        k_inter_reduce_rows<BITS, NW, C, U, false><<<dim3((uint32_t)grid), dim3(kThreads), 0, st>>>(
             P, K, m, l2, rows_per_block, dv.d, dv.recip, dv.kind, (uint32_t)per_xcd, xcd_shift, out);
     return launch_status();
 }
@@ -1603,12 +1652,11 @@ int launch_inter_rows(const PeerTable& P, int K, uint64_t m, uint32_t B, const D
 // same number of tiles and that they all start together: a launch that does not fill more
 // than a few residency rounds is cut into waves of C tiles such that all waves are resident
 // at once (one round, no second round that runs nearly empty), choosing the C that leaves
-// the fewest idle tile slots.  Resident waves per SIMD by registers and LDS: 8, 5, 4 for
-// C = 1, 2, 3.  Larger launches take C = 1 and let the dispatcher balance.
-int inter_rows_vectors(uint64_t tiles)
+// the fewest idle tile slots.  resident[C]: waves of the C-vector kernel a SIMD holds, by its
+// registers and LDS.  Larger launches take C = 1 and let the dispatcher balance.
+int inter_rows_vectors(uint64_t tiles, const uint64_t (&resident)[4])
 {
     constexpr uint64_t simds = 256 * 4;
-    constexpr uint64_t resident[4] = {0, 8, 5, 4};
     if (tiles <= resident[1] * simds || tiles > 3 * resident[3] * simds) return 1;
     int best = 1;
     uint64_t best_cost = ~0ull;
@@ -1624,20 +1672,37 @@ int inter_rows_vectors(uint64_t tiles)
     return best;
 }
 
+// The row form with NW code dwords per lane and vector, if the block is a whole number of its
+// rows of 16 lanes (blocks that are not powers of two find their scales by a 32-bit division
+// of the row index); ZPP_EINVAL if not, and nothing is launched.
+template <int BITS, int NW>
+int launch_inter_row_form(const PeerTable& P, int K, uint64_t m, uint32_t B, const Divisor& dv, float* out, hipStream_t st)
+{
+    constexpr uint32_t E = EPL<BITS, NW>::value;
+    if (B % (16 * E) != 0 || (log2_or_neg(B) < 0 && m / (16 * E) >= (1ull << 32))) return ZPP_EINVAL;
+    // resident waves per SIMD of the kernels with 1, 2, 3 vectors per wave (int4: 57, 91, 102
+    // registers; int8 with two dwords per vector: 68, 78, 120; with one: 50, 64, 76)
+    constexpr uint64_t resident[4] = {0, BITS == 4 ? 8u : (NW == 2 ? 7u : 8u), BITS == 4 ? 5u : (NW == 2 ? 6u : 8u),
+                                      BITS == 4 ? 4u : (NW == 2 ? 4u : 6u)};
+    const int c = inter_rows_vectors((m + kWave * E - 1) / (kWave * E), resident);
+    // peers per fetch group: 8 where a wave has one vector (more bytes in flight per wave), 4 otherwise
+    if (c == 1) return launch_inter_rows<BITS, NW, 1, 8>(P, K, m, B, dv, out, st);
+    if (c == 2) return launch_inter_rows<BITS, NW, 2, 4>(P, K, m, B, dv, out, st);
+    return launch_inter_rows<BITS, NW, 3, 4>(P, K, m, B, dv, out, st);
+}
+
 template <int BITS>
 int launch_inter(const PeerTable& P, int K, uint64_t m, uint32_t B, const Divisor& dv, float* out, hipStream_t st)
 {
     constexpr uint32_t E = EPL<BITS, 1>::value;
+    // A vector is 8 elements where the block allows it (int4: one code dword; int8: two, if the
+    // block is a multiple of 128), else the 4 elements of one int8 dword.
+    if constexpr (BITS == 8)
+        if (B % 128 == 0 && (log2_or_neg(B) >= 0 || m / 128 < (1ull << 32)))
+            return launch_inter_row_form<8, 2>(P, K, m, B, dv, out, st);
+    if (B % (16 * E) == 0 && (log2_or_neg(B) >= 0 || m / (16 * E) < (1ull << 32)))
+        return launch_inter_row_form<BITS, 1>(P, K, m, B, dv, out, st);
     const int l2 = log2_or_neg(B);
-    // a row of 16 lanes inside one block: the row form (blocks that are not powers of two
-    // find their scales by a 32-bit division of the row index)
-    if (B % (16 * E) == 0 && (l2 >= 0 || m / (16 * E) < (1ull << 32))) {
-        const int c = inter_rows_vectors((m + kWave * E - 1) / (kWave * E));
-        // peers per fetch group: 8 where a wave has one vector (more bytes in flight per wave), 4 otherwise
-        if (c == 1) return launch_inter_rows<BITS, 1, 8>(P, K, m, B, dv, out, st);
-        if (c == 2) return launch_inter_rows<BITS, 2, 4>(P, K, m, B, dv, out, st);
-        return launch_inter_rows<BITS, 3, 4>(P, K, m, B, dv, out, st);
-    }
     constexpr uint64_t per_wave = (uint64_t)kWave * E;
     const uint64_t waves = (m + per_wave - 1) / per_wave;
     const uint64_t grid = (waves + kWavesPerWG - 1) / kWavesPerWG;

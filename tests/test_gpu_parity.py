@@ -313,12 +313,13 @@ def test_qgz_intra_reduce_bit_exact(X, block, bits, blocks):
     assert_guards_intact(sfull, m // block, torch.float32)
 
 
-@pytest.mark.parametrize("X,block,blocks", [(8, 4096, 6), (5, 1536, 9), (2, 96, 40), (8, 512, 12)])
-def test_qgz_intra_reduce_with_scales_beyond_the_exact_int4_decode(X, block, blocks):
-    """Scales of 2^100 and more (never produced from 16-bit gradients) leave the fused int4
+@pytest.mark.parametrize("X,block,blocks,bits", [(8, 4096, 6, 4), (5, 1536, 9, 4), (2, 96, 40, 4), (8, 512, 12, 4),
+                                                 (8, 4096, 3, 8), (3, 1504, 5, 8), (8, 512, 12, 8), (4, 128, 40, 8)])
+def test_qgz_intra_reduce_with_scales_beyond_the_fused_decode(X, block, blocks, bits):
+    """Scales of 2^100 and more (never produced from 16-bit gradients) leave the fused
     decode: the block is then summed by convert and multiply.  One such scale per block, of
     either sign, in some blocks; the outputs are the oracle's bit for bit."""
-    m, bits = block * blocks, 4
+    m = block * blocks
     host, dev = _peer_inputs(X, m, block, bits, seed=31 + block)
     scales = [h[1].copy() for h in host]
     for b in range(0, blocks, 2):
@@ -631,12 +632,20 @@ def test_qgz_inter_reduce_blocks_of_whole_rows_that_are_not_powers_of_two(Y, blo
     assert_guards_intact(ofull, m, torch.float32)
 
 
-@pytest.mark.parametrize("tiles", [9216, 10240, 12289])
-def test_qgz_inter_reduce_int8_across_launch_shapes(tiles):
-    """The same launch shapes for int8 codes (a wave tile is 256 elements there)."""
-    block, bits, Y = 256, 8, 3
-    m = 256 * tiles
-    host, dev = _peer_inputs(Y, m, block, bits, seed=tiles)
+@pytest.mark.parametrize("block,elements", [
+    (256, 512 * 9216), (256, 512 * 10240), (256, 512 * 12289), (256, 512 * 8192 + 256),   # vectors of two code dwords
+    (384, 512 * 9216), (1152, 1152 * 4551),                                               # the same, block not a power of two
+    (64, 256 * 9216), (64, 256 * 10240), (64, 256 * 12289),                               # vectors of one code dword
+    (192, 256 * 9216), (320, 320 * 8193),
+])
+def test_qgz_inter_reduce_int8_across_launch_shapes(block, elements):
+    """The same launch shapes for int8 codes.  Blocks that are multiples of 128 take vectors of
+    two code dwords (a wave tile is 512 elements), other multiples of 64 vectors of one (256
+    elements); one, two and three vectors per wave in each form."""
+    bits, Y = 8, 3
+    m = elements
+    assert m % block == 0
+    host, dev = _peer_inputs(Y, m, block, bits, seed=block)
     want = oracle.qgz_inter_reduce([h[0] for h in host], [h[1] for h in host], m, block, bits, 24.0)
     ofull, out = guarded(m, torch.float32)
     zpp.qgz_inter_reduce([d[0] for d in dev], [d[1] for d in dev], m, block, bits, 24.0, out=out)
@@ -645,15 +654,17 @@ def test_qgz_inter_reduce_int8_across_launch_shapes(tiles):
     assert_guards_intact(ofull, m, torch.float32)
 
 
-@pytest.mark.parametrize("blocks,huge", [(40, 2.0 ** 70), (9216, 2.0 ** 70), (9216, 2.0 ** 101), (10240, 2.0 ** 120)])
-def test_qgz_inter_reduce_with_scales_outside_the_short_division_range(blocks, huge):
+@pytest.mark.parametrize("blocks,huge,bits", [(40, 2.0 ** 70, 4), (9216, 2.0 ** 70, 4), (9216, 2.0 ** 101, 4), (10240, 2.0 ** 120, 4),
+                                              (40, 2.0 ** 101, 8), (9216, 2.0 ** 70, 8), (9216, 2.0 ** 110, 8), (10240, 2.0 ** 101, 8)])
+def test_qgz_inter_reduce_with_scales_outside_the_short_division_range(blocks, huge, bits):
     """Tiny (2^-40) and subnormal scales, and huge ones, keep the plain division; scales of
-    2^100 and more also leave the exact int4 decode (every lane then decodes with its own scale
-    loads), at one and at several vectors per wave.  The result is the oracle's bit for bit."""
-    block, bits, Y = 512, 4, 6
+    2^100 and more also leave the fused decode (every lane then decodes with its own scale
+    loads, by convert and multiply), at one and at several vectors per wave, for both code
+    widths (every code value occurs, -8 and -128 included).  The result is the oracle's bit for bit."""
+    block, Y = (512 if bits == 4 else 256), 6
     m = block * blocks
     rng = np.random.default_rng(7)
-    codes = [rng.integers(0, 256, size=m // 2, dtype=np.uint8) for _ in range(Y)]
+    codes = [rng.integers(0, 256, size=m * bits // 8, dtype=np.uint8) for _ in range(Y)]
     scales = []
     for k in range(Y):
         s = (10.0 ** rng.uniform(-4, 0, size=blocks)).astype(np.float32)
