@@ -876,7 +876,7 @@ __device__ __forceinline__ void reduce_peers(const PeerTable& P, int K, uint64_t
 }
 
 // The same sum with one peer at a time and convert-and-multiply decodes: the path of the
-// row-form kernels for scales their exact int4 decode cannot take.
+// row-form kernels for scales their fused decode cannot take.
 template <int BITS, int NW>
 __device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, uint64_t e, uint64_t blk,
                                                    float (&acc)[(EPL<BITS, NW>::value)])
@@ -901,7 +901,7 @@ __device__ __forceinline__ void reduce_peers_plain(const PeerTable& P, int K, ui
 // row (lanes 16r .. 16r+15) decode with one scale per peer, and the scales travel through
 // LDS instead of through per-lane loads: before the first peer, lane j of each row fetches
 // the scales of peers j, j+16, j+32, j+48 for the row's block (a few wave-wide loads cover
-// all peers), derives the operands of the int4 decode for them and parks them in a table
+// all peers), derives the operands of the fused decode for them and parks them in a table
 // of the wave; each peer's operands are then read back with one broadcast LDS read per
 // row.  That takes the scale load, its address arithmetic and the three multiplies per
 // peer and lane off the vector ALU, which is what bounds this kernel.  (The intra-node stage
