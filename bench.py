@@ -85,7 +85,7 @@ def profile_figures(name, kernel, elements):
         parts = line.split()
         if len(parts) >= 2 and parts[0] == "SOURCE":
             facts.update(p.split("=", 1) for p in parts[1:] if "=" in p)
-        if len(parts) >= 3 and parts[0] in ("TRAFFIC", "VALU"):
+        if len(parts) >= 3 and parts[0] in ("TRAFFIC", "VALU", "TRACE"):
             rows[parts[1]] = dict(p.split("=", 1) for p in parts[2:] if "=" in p)
     if facts.get("sha256") != want_hash:
         return None, dict(src, refused="summary was taken from another version of the kernel source")
@@ -262,6 +262,15 @@ def main():
             kernels[k]["valu_source"] = source
         else:
             kernels[k]["valu_source"] = source
+        # the same kernel's duration in the committed rocprofv3 kernel trace of this benchmark (dispatch
+        # time stamps, no event between the launches); an earlier run, hence with its source
+        row, source = profile_figures("bench_step_kernel_stats.txt", k, elements_per[k])
+        if row is not None:
+            us = float(row["avg_us"])
+            kernels[k]["kernel_trace"] = dict(source, avg_us=us, calls=int(row["calls"]),
+                                              frac_of_hbm_peak=round(bytes_per[k] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+        else:
+            kernels[k]["kernel_trace"] = source
 
     # the same step captured once into a HIP graph (kernel nodes only) and replayed
     graph = None
