@@ -537,13 +537,15 @@ def test_decoders_accept_every_code_value(bits, block):
     assert eq_bytes(out, oracle.qgz_inter_reduce(codes, scales, n, block, bits, 3.0))
 
 
+@pytest.mark.parametrize("block", [512, 96, 4096, 64, 256])
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("K", [1, 3])
-def test_reduce_stages_return_plus_zero_for_zero_products(bits, K):
+def test_reduce_stages_return_plus_zero_for_zero_products(bits, K, block):
     """Products that are -0 (code 0 times a negative scale, a negative code times a zero scale
     of either sign) must not leak their sign: every sum starts from +0, so both stages return
-    +0 bits, exactly as the oracle does, also with a single peer."""
-    block, blocks = 512, 6
+    +0 bits, exactly as the oracle does, also with a single peer, in every kernel the block
+    size selects, and also where a scale of 2^101 sends a block to the convert-and-multiply path."""
+    blocks = 8
     n = block * blocks
     rng = np.random.default_rng(99 + bits + K)
     codes, scales = [], []
@@ -556,16 +558,20 @@ def test_reduce_stages_return_plus_zero_for_zero_products(bits, K):
         s[3] = -0.0                      # block 3: positive codes, -0 scale
         s[4] = 0.5                       # block 4: ordinary values
         s[5] = -1e-3                     # block 5: ordinary values, negative scale
+        s[6] = -(2.0 ** 101)             # block 6: code 0, a negative scale beyond the fused decode
+        s[7] = 2.0 ** 101                # block 7: ordinary values at such a scale
         per = block * bits // 8
         c[per:3 * per] = 0x99 if bits == 4 else 0xF9           # -7 in every field
         c[3 * per:4 * per] = 0x33 if bits == 4 else 0x05
-        c[4 * per:] = rng.integers(0, 256, size=2 * per, dtype=np.uint8)
+        c[4 * per:6 * per] = rng.integers(0, 256, size=2 * per, dtype=np.uint8)
+        c[7 * per:] = rng.integers(0, 256, size=per, dtype=np.uint8)
         codes.append(c)
         scales.append(s)
     dcodes = [torch.from_numpy(c).to(DEV) for c in codes]
     dscales = [torch.from_numpy(s).to(DEV) for s in scales]
     want = oracle.qgz_inter_reduce(codes, scales, n, block, bits, 1.0)
     assert not np.signbit(want[:4 * block]).any() and (want[:4 * block] == 0).all()
+    assert not np.signbit(want[6 * block:7 * block]).any() and (want[6 * block:7 * block] == 0).all()
     got = zpp.qgz_inter_reduce(dcodes, dscales, n, block, bits, 1.0)
     torch.cuda.synchronize()
     assert eq_bytes(got, want)
